@@ -1,0 +1,270 @@
+"""FastGen hot path -- plain float64 CPU oracle.  TEST INFRASTRUCTURE ONLY.
+
+This file is the checker, not the product. Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the HIP library never does, and nothing here imports the HIP
+library or shares code, tables or constants with it.
+
+It writes out, densely and in float64, what the paper defines for ONE attention head
+("unit") at a time:
+
+  * Alg. 1 / Sec. 3.3: the attention map A = softmax(Q K^T) of the prompt (causal,
+    scaled -- decoder-only attention, Sec. 3.1);
+  * Sec. 3.4: the four base policies (special, punctuation, local, frequent) and the
+    hybrid policy family of Eq. 2, "+" meaning union of kept sets;
+  * Eq. 1: the cheapest policy of the family whose recovery reaches T;
+  * Alg. 1: the compressed cache f(K, V, C);
+  * Alg. 2: one decode step over the compressed cache followed by re-application of f.
+
+Readings taken where the paper is silent (each is a *reading*, stated once here):
+  R1  softmax is causal and uses a scale (default 1/sqrt(d)).
+  R2  the norm in Eq. 1 is the mean over query rows of the total-variation distance between
+      a row of A and the same row restricted to the kept tokens and renormalised; that
+      distance equals 1 - (kept mass of the row), so "recovers A with ratio T" <=> the mean
+      kept attention mass is >= T (matches Sec. 4: "accumulated attention score on special
+      tokens is higher than 0.95").
+  R3  on the prompt, `frequent` is the hindsight top-k of the complete column sums and
+      `local` is row-relative (row i keeps columns i-w+1..i).
+  R4  frequent's budget is counted over all held tokens and then united with the other sets
+      (overlap allowed); k_f(L) = floor(r_f * L) follows the *current* length L, the local
+      window w = max(1, floor(r_l * n)) is fixed by the *input* length n (Sec. 3.4).
+  R5  budgets are floor() of the IEEE-double product.
+  R6  ties: equal cost -> smaller policy id; equal score -> keep the smaller position.
+  R7  decode step t handles a new token at position n+t; it attends to itself; its score
+      starts at 0 and receives this step's attention like every other held token; scores
+      are only maintained for policies that contain `frequent`.
+  R8  R >= T (non-strict), as Eq. 1's "<=".
+
+Pinned by tests/test_oracle_pins.py (closed forms for Q = 0, brute force over subsets,
+textbook softmax/attention, TV-distance identity, nestedness, full-cache invariants).
+Parity unpinned (no number in the paper distinguishes the alternatives): readings R3, R4,
+R6, R7 themselves.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+import numpy as np
+
+POLICY_NAMES = ("special", "special+punct", "special+punct+frequent",
+                "special+punct+frequent+local", "full")
+N_POLICIES = 5
+CLASS_SPECIAL = 1
+CLASS_PUNCT = 2
+
+
+# ----------------------------------------------------------------------------------------
+# budgets (Sec. 3.4: ratios r_l, r_f)
+# ----------------------------------------------------------------------------------------
+
+def local_window(r_l: float, n: int) -> int:
+    """w: length budget of local context, a ratio of the INPUT sequence length."""
+    return max(1, int(math.floor(float(r_l) * float(n))))
+
+
+def frequent_budget(r_f: float, L: int) -> int:
+    """k_f(L): length budget of frequent tokens, a ratio of the CURRENT sequence length."""
+    return int(math.floor(float(r_f) * float(L)))
+
+
+# ----------------------------------------------------------------------------------------
+# Alg. 1, line "A <- softmax(Q K^T)"
+# ----------------------------------------------------------------------------------------
+
+def attention_map(Q: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
+    """Dense causal attention map of one head, float64, rows sum to 1."""
+    Q = np.asarray(Q, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    n = Q.shape[0]
+    s = (Q @ K.T) * float(scale)
+    causal = np.tril(np.ones((n, n), dtype=bool))
+    s = np.where(causal, s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    e = np.exp(s)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def top_k_positions(score: np.ndarray, pos: np.ndarray, k: int) -> np.ndarray:
+    """Positions of the k largest scores; equal scores -> the smaller position wins."""
+    if k <= 0:
+        return np.zeros(0, dtype=np.int64)
+    order = np.lexsort((pos, -score))       # primary -score, secondary pos
+    return np.sort(pos[order[:k]])
+
+
+def boundary_gap(score: np.ndarray, k: int) -> float:
+    """Relative gap between the k-th and (k+1)-th largest score (inf if no boundary)."""
+    m = score.size
+    if k <= 0 or k >= m:
+        return math.inf
+    s = np.sort(score)[::-1]
+    hi, lo = s[k - 1], s[k]
+    return float((hi - lo) / hi) if hi > 0 else 0.0
+
+
+# ----------------------------------------------------------------------------------------
+# Sec. 3.4 policies on the prompt, Eq. 2 family, Eq. 1 selection
+# ----------------------------------------------------------------------------------------
+
+@dataclass
+class Profile:
+    policy: int
+    recovery: np.ndarray        # [5] float64, R_c
+    cost: np.ndarray            # [5] int64, |K_c| at the end of the prompt
+    kept: np.ndarray            # sorted positions of K_policy
+    colsum: np.ndarray          # [n] cumulative attention score of every prompt token
+    window: int
+    k_f: int
+    margin: float               # min_c<4 |R_c - T|
+    topk_gap: float             # relative gap at the frequent boundary
+    sets: List[np.ndarray] = field(default_factory=list)  # K_0..K_4 (sorted positions)
+
+
+def kept_sets(cls: np.ndarray, colsum: np.ndarray, r_l: float, r_f: float) -> List[np.ndarray]:
+    """K_0..K_4 at the end of the prompt: unions in the order of Eq. 2."""
+    n = colsum.size
+    pos = np.arange(n, dtype=np.int64)
+    special = pos[(cls & CLASS_SPECIAL) != 0]
+    punct = pos[(cls & CLASS_PUNCT) != 0]
+    freq = top_k_positions(colsum, pos, frequent_budget(r_f, n))
+    w = local_window(r_l, n)
+    local = pos[max(0, n - w):]
+    K0 = special
+    K1 = np.union1d(K0, punct)
+    K2 = np.union1d(K1, freq)
+    K3 = np.union1d(K2, local)
+    return [K0, K1, K2, K3, pos]
+
+
+def recovery_dense(A: np.ndarray, static_keep: np.ndarray, window: int) -> float:
+    """Mean over query rows of the attention mass on kept tokens. `static_keep` is a
+    boolean column mask; window > 0 additionally keeps columns i-window+1..i of row i."""
+    n = A.shape[0]
+    i = np.arange(n)[:, None]
+    j = np.arange(n)[None, :]
+    keep = np.broadcast_to(static_keep[None, :], (n, n)) & (j <= i)
+    if window > 0:
+        keep = keep | ((j <= i) & (j > i - window))
+    kept_mass_per_row = np.where(keep, A, 0.0).sum(axis=1)
+    return float(kept_mass_per_row.mean())
+
+
+def select_policy(cost: np.ndarray, recovery: np.ndarray, T: float) -> int:
+    """Eq. 1: argmin cost subject to recovery >= T; equal cost -> smaller id."""
+    best = -1
+    for c in range(N_POLICIES):
+        # C_full is the uncompressed cache: its difference to A is zero by definition
+        feasible = (c == N_POLICIES - 1) or (recovery[c] >= T)
+        if feasible and (best < 0 or cost[c] < cost[best]):
+            best = c
+    return best
+
+
+def profile_unit(Q: np.ndarray, K: np.ndarray, cls: np.ndarray, T: float, r_l: float,
+                 r_f: float, scale: float, forced_policy: int = -1) -> Profile:
+    """Alg. 1 up to the choice of C for one head."""
+    A = attention_map(Q, K, scale)
+    n = A.shape[0]
+    colsum = A.sum(axis=0)
+    sets = kept_sets(np.asarray(cls), colsum, r_l, r_f)
+    w = local_window(r_l, n)
+    rec = np.zeros(N_POLICIES)
+    for c in range(N_POLICIES):
+        mask = np.zeros(n, dtype=bool)
+        # the static part of K_3 is K_2: its local component is row-relative
+        mask[sets[min(c, 2)] if c < 4 else sets[4]] = True
+        rec[c] = recovery_dense(A, mask, w if c == 3 else 0)
+    cost = np.array([s.size for s in sets], dtype=np.int64)
+    policy = select_policy(cost, rec, T) if forced_policy < 0 else int(forced_policy)
+    return Profile(policy=policy, recovery=rec, cost=cost, kept=sets[policy], colsum=colsum,
+                   window=w, k_f=frequent_budget(r_f, n),
+                   margin=float(np.min(np.abs(rec[:4] - T))),
+                   topk_gap=boundary_gap(colsum, frequent_budget(r_f, n)), sets=sets)
+
+
+# ----------------------------------------------------------------------------------------
+# Alg. 1 compaction f(K, V, C) and Alg. 2 decode step
+# ----------------------------------------------------------------------------------------
+
+@dataclass
+class Cache:
+    """Compressed cache of one head: held tokens in ascending position order."""
+    policy: int
+    n: int                      # prompt length (fixes the local window)
+    K: np.ndarray               # [len, d]
+    V: np.ndarray               # [len, d]
+    score: np.ndarray           # [len] cumulative attention score
+    pos: np.ndarray             # [len] int64
+    cls: np.ndarray             # [len] uint8
+    min_gap: float = math.inf   # smallest relative top-k boundary gap seen while decoding
+    fragile_step: int = -1      # first decode step whose boundary gap fell below `gap_eps`
+
+
+def compact_unit(K: np.ndarray, V: np.ndarray, cls: np.ndarray, prof: Profile) -> Cache:
+    keep = prof.kept
+    return Cache(policy=prof.policy, n=K.shape[0],
+                 K=np.asarray(K, dtype=np.float64)[keep].copy(),
+                 V=np.asarray(V, dtype=np.float64)[keep].copy(),
+                 score=prof.colsum[keep].copy(), pos=keep.copy(),
+                 cls=np.asarray(cls, dtype=np.uint8)[keep].copy())
+
+
+def kept_after_step(policy: int, pos: np.ndarray, cls: np.ndarray, score: np.ndarray,
+                    p_new: int, window: int, r_f: float) -> np.ndarray:
+    """Boolean mask over held tokens: which stay after the token at position p_new."""
+    if policy == 4:
+        return np.ones(pos.size, dtype=bool)
+    keep = (cls & CLASS_SPECIAL) != 0
+    if policy >= 1:
+        keep |= (cls & CLASS_PUNCT) != 0
+    if policy >= 2:
+        top = top_k_positions(score, pos, frequent_budget(r_f, p_new + 1))
+        keep |= np.isin(pos, top)
+    if policy >= 3:
+        keep |= pos > p_new - window
+    return keep
+
+
+def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, cls_new: int,
+                t: int, r_l: float, r_f: float, scale: float, gap_eps: float = 0.0) -> np.ndarray:
+    """One pass of Alg. 2's inner body for one head; returns the attention output o."""
+    p = c.n + t
+    c.K = np.vstack([c.K, np.asarray(k_new, dtype=np.float64)[None, :]])
+    c.V = np.vstack([c.V, np.asarray(v_new, dtype=np.float64)[None, :]])
+    c.score = np.append(c.score, 0.0)
+    c.pos = np.append(c.pos, p)
+    c.cls = np.append(c.cls, np.uint8(cls_new))
+    s = (c.K @ np.asarray(q, dtype=np.float64)) * float(scale)
+    e = np.exp(s - s.max())
+    a = e / e.sum()
+    o = a @ c.V
+    if c.policy in (2, 3):
+        c.score = c.score + a
+        g = boundary_gap(c.score, frequent_budget(r_f, p + 1))
+        c.min_gap = min(c.min_gap, g)
+        if g < gap_eps and c.fragile_step < 0:
+            c.fragile_step = t
+    keep = kept_after_step(c.policy, c.pos, c.cls, c.score, p, local_window(r_l, c.n), r_f)
+    c.K, c.V, c.score, c.pos, c.cls = c.K[keep], c.V[keep], c.score[keep], c.pos[keep], c.cls[keep]
+    return o
+
+
+def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, scale,
+             forced_policy: int = -1, gap_eps: float = 0.0, record_states: bool = False) -> Dict:
+    """Whole path for one head: profile, compact, S decode steps."""
+    prof = profile_unit(Q, K, cls, T, r_l, r_f, scale, forced_policy)
+    cache = compact_unit(K, V, cls, prof)
+    S = 0 if q_steps is None else len(q_steps)
+    d = np.asarray(K).shape[1]
+    outs = np.zeros((S, d))
+    lens = np.zeros(S, dtype=np.int64)
+    states: List[np.ndarray] = []
+    init_pos = cache.pos.copy()
+    for t in range(S):
+        outs[t] = decode_step(cache, q_steps[t], k_steps[t], v_steps[t], int(cls_steps[t]),
+                              t, r_l, r_f, scale, gap_eps)
+        lens[t] = cache.pos.size
+        if record_states:
+            states.append(cache.pos.copy())
+    return dict(profile=prof, init_pos=init_pos, outs=outs, lens=lens, states=states, cache=cache)

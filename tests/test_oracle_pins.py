@@ -1,0 +1,422 @@
+"""Pins for the float64 oracle: every check here compares the oracle with something that
+is NOT the oracle -- exact rational closed forms, brute force over subsets, textbook
+softmax/attention from another library, or a from-scratch recomputation by loops."""
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastgen_oracle as fo
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rand_unit(seed, n, d, p_punct=0.15, bias=None):
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((n, d))
+    K = rng.standard_normal((n, d))
+    V = rng.standard_normal((n, d))
+    cls = np.zeros(n, dtype=np.uint8)
+    cls[0] = 1
+    cls[1:][rng.random(n - 1) < p_punct] = 2
+    if bias is not None:
+        K[:, 0] = np.where(cls != 0, bias, 0.0)
+        Q[:, 0] = 1.0
+    return Q, K, V, cls
+
+
+def harmonic(k):
+    return sum(Fraction(1, i) for i in range(1, k + 1))
+
+
+# ---------------------------------------------------------------- A (Alg. 1, Sec. 3.3)
+
+def test_attention_map_is_textbook_causal_softmax():
+    Q, K, _, _ = rand_unit(1, 37, 16)
+    scale = 0.25
+    A = fo.attention_map(Q, K, scale)
+    s = torch.from_numpy(Q) @ torch.from_numpy(K).T * scale
+    s = s.masked_fill(torch.triu(torch.ones(37, 37, dtype=torch.bool), 1), float("-inf"))
+    ref = torch.softmax(s, dim=1).numpy()
+    assert np.allclose(A, ref, rtol=0, atol=1e-14)
+    assert np.allclose(A.sum(1), 1.0, atol=1e-14)
+    assert np.all(A[np.triu_indices(37, 1)] == 0.0)
+    assert abs(A.sum() - 37) < 1e-12          # sum_j colsum_j = n
+    # Q K^T, not K Q^T: row i is the distribution of QUERY i
+    i = 20
+    row = np.exp(scale * (K[: i + 1] @ Q[i]))
+    assert np.allclose(A[i, : i + 1], row / row.sum(), atol=1e-14)
+
+
+def test_golden_q0_n4_worked_example():
+    """Uniform causal attention (Q = 0): A_ij = 1/(i+1). Values derived by hand in exact
+    rationals and stored in tests/golden/q0_n4.txt."""
+    vals = {}
+    with open(os.path.join(GOLDEN, "q0_n4.txt")) as f:
+        for line in f:
+            if line.startswith("#") or not line.strip():
+                continue
+            k, v = line.split("=")
+            vals[k.strip()] = [Fraction(x) for x in v.split()]
+    n, d = 4, 8
+    Q = np.zeros((n, d))
+    K = np.random.default_rng(0).standard_normal((n, d))
+    cls = np.array([1, 0, 0, 0], dtype=np.uint8)
+    A = fo.attention_map(Q, K, 1.0)
+    assert np.allclose(A.sum(0), [float(x) for x in vals["colsum"]], atol=1e-15)
+    keep0 = np.array([True, False, False, False])
+    assert abs(fo.recovery_dense(A, keep0, 0) - float(vals["R_special"][0])) < 1e-15
+    assert abs(fo.recovery_dense(A, keep0, 1) - float(vals["R_special_local_w1"][0])) < 1e-15
+    # frequent with k_f = 2 -> positions {0, 1}
+    assert list(fo.top_k_positions(A.sum(0), np.arange(4), 2)) == [0, 1]
+    keepf = np.array([True, True, False, False])
+    assert abs(fo.recovery_dense(A, keepf, 0) - float(vals["R_freq_k2"][0])) < 1e-15
+    # through the full profile: r_f = 0.5 -> k_f = 2, r_l = 0.25 -> w = 1
+    p = fo.profile_unit(Q, K, cls, 0.75, 0.25, 0.5, 1.0)
+    assert p.k_f == 2 and p.window == 1
+    assert np.allclose(p.recovery, [float(x) for x in vals["R_family"]], atol=1e-15)
+    assert list(p.cost) == [1, 1, 2, 3, 4]
+    assert p.policy == 2            # 38/48 >= 0.75, cost 2
+    assert list(p.kept) == [0, 1]
+
+
+@pytest.mark.parametrize("n,w,k", [(9, 3, 2), (64, 7, 19), (50, 50, 0)])
+def test_q0_closed_forms_harmonic(n, w, k):
+    """Q = 0: colsum_j = H_n - H_j, band sum_j = H_min(j+w,n) - H_j; frequent = first k."""
+    Q = np.zeros((n, 4))
+    K = np.ones((n, 4))
+    A = fo.attention_map(Q, K, 0.5)
+    H = [harmonic(i) for i in range(n + 1)]
+    colsum = [H[n] - H[j] for j in range(n)]
+    assert np.allclose(A.sum(0), [float(c) for c in colsum], atol=1e-13)
+    top = fo.top_k_positions(A.sum(0), np.arange(n), k)
+    assert list(top) == list(range(k))
+    static = np.zeros(n, dtype=bool)
+    static[:k] = True
+    band = [H[min(j + w, n)] - H[j] for j in range(n)]
+    expect = (sum(colsum[:k]) + sum(band[k:])) / n
+    assert abs(fo.recovery_dense(A, static, w) - float(expect)) < 1e-13
+    expect_static = sum(colsum[:k]) / n
+    assert abs(fo.recovery_dense(A, static, 0) - float(expect_static)) < 1e-13
+
+
+def test_one_hot_head_selects_special():
+    Q, K, _, cls = rand_unit(3, 40, 8, bias=None)
+    K[:, 0] = 0.0
+    K[0, 0] = 200.0
+    Q[:, 0] = 1.0
+    p = fo.profile_unit(Q, K, cls, 0.95, 0.3, 0.3, 1.0)
+    assert p.policy == 0 and abs(p.recovery[0] - 1.0) < 1e-12
+    assert list(p.kept) == [0]
+
+
+# ---------------------------------------------------------------- Eq. 1 <=> kept mass
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_eq1_distance_equals_one_minus_kept_mass(seed):
+    """Brute force of Eq. 1's constraint: softmax over the kept keys only, half the L1
+    distance to the full row, averaged over rows == 1 - R_c."""
+    n, d = 24, 8
+    Q, K, _, cls = rand_unit(seed, n, d, bias=2.0)
+    scale = 1 / math.sqrt(d)
+    prof = fo.profile_unit(Q, K, cls, 0.9, 0.25, 0.25, scale)
+    A = fo.attention_map(Q, K, scale)
+    w = prof.window
+    for c in range(5):
+        static = set(prof.sets[min(c, 2)].tolist()) if c < 4 else set(range(n))
+        dist = 0.0
+        for i in range(n):
+            kept = {j for j in static if j <= i}
+            if c == 3:
+                kept |= {j for j in range(max(0, i - w + 1), i + 1)}
+            kept = sorted(kept)
+            assert kept, "position 0 is special"
+            logits = np.array([scale * Q[i] @ K[j] for j in kept])
+            e = np.exp(logits - logits.max())
+            a_c = np.zeros(n)
+            a_c[kept] = e / e.sum()
+            dist += 0.5 * np.abs(A[i] - a_c).sum()
+        assert abs(dist / n - (1.0 - prof.recovery[c])) < 1e-12
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_dense_recovery_equals_column_and_band_sums(seed):
+    n, d = 33, 8
+    Q, K, _, cls = rand_unit(10 + seed, n, d, bias=1.5)
+    prof = fo.profile_unit(Q, K, cls, 0.9, 0.2, 0.3, 0.3)
+    A = fo.attention_map(Q, K, 0.3)
+    w = prof.window
+    colsum = np.array([sum(A[i, j] for i in range(n)) for j in range(n)])
+    band = np.array([sum(A[i, j] for i in range(j, min(j + w, n))) for j in range(n)])
+    assert np.allclose(prof.colsum, colsum, atol=1e-14)
+    for c in range(3):
+        assert abs(prof.recovery[c] - colsum[prof.sets[c]].sum() / n) < 1e-13
+    in2 = np.zeros(n, dtype=bool)
+    in2[prof.sets[2]] = True
+    r3 = (colsum[in2].sum() + band[~in2].sum()) / n
+    assert abs(prof.recovery[3] - r3) < 1e-13
+    assert abs(prof.recovery[4] - 1.0) < 1e-14
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_nested_sets_and_monotone(seed):
+    n, d = 48, 8
+    Q, K, _, cls = rand_unit(20 + seed, n, d, bias=float(seed))
+    prof = fo.profile_unit(Q, K, cls, 0.95, 0.3, 0.3, 0.35)
+    for a, b in zip(prof.sets[:-1], prof.sets[1:]):
+        assert set(a.tolist()) <= set(b.tolist())
+    assert np.all(np.diff(prof.cost) >= 0)
+    assert np.all(np.diff(prof.recovery) >= -1e-15)
+    assert prof.cost[4] == n and abs(prof.recovery[4] - 1) < 1e-14
+    assert list(prof.kept) == sorted(prof.sets[prof.policy].tolist())
+
+
+# ---------------------------------------------------------------- selection (Eq. 1 / Eq. 2)
+
+@pytest.mark.parametrize("seed", range(8))
+def test_selection_matches_brute_force_over_unions(seed):
+    """All 16 unions of {special, punct, frequent, local}: cost and recovery from dense A by
+    loops. Restricted to the members of Eq. 2's family the literal argmin equals both the
+    oracle's choice and the greedy first-hit scan (App. A.1)."""
+    n, d = 20, 4
+    T = [0.6, 0.8, 0.9, 0.95][seed % 4]
+    Q, K, _, cls = rand_unit(40 + seed, n, d, p_punct=0.2, bias=[0.0, 2.0, 4.0, 8.0][seed // 2])
+    scale, r_l, r_f = 0.5, 0.25, 0.2
+    prof = fo.profile_unit(Q, K, cls, T, r_l, r_f, scale)
+    A = fo.attention_map(Q, K, scale)
+    w = max(1, math.floor(r_l * n))
+    k = math.floor(r_f * n)
+    colsum = A.sum(0)
+    ranked = sorted(range(n), key=lambda j: (-colsum[j], j))
+    base = {
+        "s": {j for j in range(n) if cls[j] & 1},
+        "p": {j for j in range(n) if cls[j] & 2},
+        "f": set(ranked[:k]),
+    }
+    table = {}
+    for r in range(5):
+        for combo in itertools.combinations("spfl", r):
+            static = set().union(*[base[x] for x in combo if x != "l"]) if combo else set()
+            use_local = "l" in combo
+            end_set = static | (set(range(n - w, n)) if use_local else set())
+            rec = 0.0
+            for i in range(n):
+                cols = {j for j in static if j <= i}
+                if use_local:
+                    cols |= set(range(max(0, i - w + 1), i + 1))
+                rec += sum(A[i, j] for j in cols)
+            table["".join(combo)] = (len(end_set), rec / n)
+    family = ["s", "sp", "spf", "spfl"]
+    cands = [(table[f][0], c) for c, f in enumerate(family) if table[f][1] >= T] + [(n, 4)]
+    brute = min(cands)[1]
+    first_hit = next((c for c, f in enumerate(family) if table[f][1] >= T), 4)
+    assert prof.policy == brute == first_hit
+    for c, f in enumerate(family):
+        assert prof.cost[c] == table[f][0]
+        assert abs(prof.recovery[c] - table[f][1]) < 1e-13
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_chosen_cost_not_below_best_static_subset(seed):
+    """n <= 12: enumerate all 2^n static token subsets; the cheapest one reaching T is a
+    lower bound for the cost of any static member of the family that reaches T."""
+    n, d, T = 10, 4, 0.8
+    Q, K, _, cls = rand_unit(60 + seed, n, d, bias=3.0)
+    prof = fo.profile_unit(Q, K, cls, T, 0.2, 0.3, 0.5)
+    colsum = fo.attention_map(Q, K, 0.5).sum(0)
+    best = n
+    for mask in range(1 << n):
+        idx = [j for j in range(n) if mask >> j & 1]
+        if colsum[idx].sum() / n >= T:
+            best = min(best, len(idx))
+    if prof.policy <= 2:
+        assert prof.cost[prof.policy] >= best
+    # and the family's static members reach T only with at least that many tokens
+    for c in range(3):
+        if prof.recovery[c] >= T:
+            assert prof.cost[c] >= best
+
+
+def test_cost_tie_prefers_smaller_policy_id():
+    # no punctuation at all: |K_1| = |K_0| and R_1 = R_0 -> policy 0, not 1
+    Q, K, _, cls = rand_unit(7, 30, 4, p_punct=0.0)
+    K[:, 0] = 0
+    K[0, 0] = 50
+    Q[:, 0] = 1
+    p = fo.profile_unit(Q, K, cls, 0.9, 0.3, 0.3, 1.0)
+    assert p.cost[0] == p.cost[1] and p.policy == 0
+    assert fo.select_policy(np.array([3, 3, 5, 9, 20]), np.array([.96, .96, .97, .99, 1.]), .95) == 0
+    assert fo.select_policy(np.array([3, 4, 5, 9, 20]), np.array([.5, .96, .97, .99, 1.]), .95) == 1
+    assert fo.select_policy(np.array([3, 4, 5, 9, 20]), np.array([.5, .6, .7, .8, 1.]), .95) == 4
+    assert fo.select_policy(np.array([3, 4, 5, 9, 20]), np.array([.5, .6, .95, .99, 1.]), .95) == 2
+
+
+def test_top_k_ties_and_full_sort():
+    rng = np.random.default_rng(5)
+    score = rng.integers(0, 6, size=40).astype(np.float64)   # many ties
+    pos = rng.permutation(100)[:40]
+    for k in [0, 1, 7, 39, 40, 55]:
+        ref = sorted(sorted(range(40), key=lambda i: (-score[i], pos[i]))[:k], key=lambda i: pos[i])
+        assert list(fo.top_k_positions(score, pos, k)) == [pos[i] for i in ref]
+    assert fo.boundary_gap(np.array([4.0, 1.0, 2.0]), 1) == 0.5
+    assert fo.boundary_gap(np.array([4.0, 1.0, 2.0]), 3) == math.inf
+
+
+def test_budgets_floor_against_exact_rationals():
+    for r, rs in [(0.1, "1/10"), (0.3, "3/10"), (0.25, "1/4")]:
+        fr = Fraction(rs)
+        for L in range(1, 20001):
+            exact = (fr * L).numerator // (fr * L).denominator
+            assert fo.frequent_budget(r, L) == exact, (r, L)
+            assert fo.local_window(r, L) == max(1, exact), (r, L)
+
+
+# ---------------------------------------------------------------- compaction and decode
+
+def test_compaction_rows_identical_and_ascending():
+    n, d = 40, 8
+    Q, K, V, cls = rand_unit(70, n, d, bias=4.0)
+    prof = fo.profile_unit(Q, K, cls, 0.9, 0.2, 0.2, 0.35)
+    c = fo.compact_unit(K, V, cls, prof)
+    assert np.all(np.diff(c.pos) > 0)
+    assert c.pos.size == prof.cost[prof.policy]
+    for slot, j in enumerate(c.pos):
+        assert np.array_equal(c.K[slot], K[j]) and np.array_equal(c.V[slot], V[j])
+        assert c.score[slot] == prof.colsum[j] and c.cls[slot] == cls[j]
+
+
+def _decode_inputs(seed, S, d):
+    rng = np.random.default_rng(seed)
+    q, k, v = (rng.standard_normal((S, d)) for _ in range(3))
+    cls = np.where(rng.random(S) < 0.2, 2, 0).astype(np.uint8)
+    return q, k, v, cls
+
+
+def test_full_policy_decode_is_dense_attention():
+    n, d, S = 24, 8, 10
+    Q, K, V, cls = rand_unit(80, n, d)
+    q, k, v, cn = _decode_inputs(81, S, d)
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, 0.3, 0.3, 0.4, forced_policy=4)
+    assert res["profile"].recovery[4] == pytest.approx(1.0, abs=1e-14)
+    for t in range(S):
+        Kt = torch.from_numpy(np.vstack([K, k[: t + 1]]))
+        Vt = torch.from_numpy(np.vstack([V, v[: t + 1]]))
+        a = torch.softmax(Kt @ torch.from_numpy(q[t]) * 0.4, dim=0)
+        assert np.allclose(res["outs"][t], (a @ Vt).numpy(), atol=1e-13)
+        assert res["lens"][t] == n + t + 1
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_special_punct_decode_holds_only_those_classes(policy):
+    n, d, S = 30, 8, 12
+    Q, K, V, cls = rand_unit(82, n, d, p_punct=0.3)
+    q, k, v, cn = _decode_inputs(83, S, d)
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, 0.3, 0.3, 0.4, forced_policy=policy,
+                      record_states=True)
+    bits = 1 if policy == 0 else 3
+    allcls = np.concatenate([cls, cn])
+    allK, allV = np.vstack([K, k]), np.vstack([V, v])
+    for t in range(S):
+        expect = [j for j in range(n + t + 1) if allcls[j] & bits]
+        assert list(res["states"][t]) == expect
+        held = [j for j in range(n + t) if allcls[j] & bits] + [n + t]   # new token attends to itself
+        lg = np.array([0.4 * q[t] @ allK[j] for j in held])
+        a = np.exp(lg - lg.max())
+        a /= a.sum()
+        assert np.allclose(res["outs"][t], a @ allV[held], atol=1e-13)
+
+
+def test_local_only_decode_is_sliding_window_attention():
+    """policy 3 with r_f = 0 and no special/punct tokens: textbook windowed attention."""
+    n, d, S = 30, 8, 15
+    Q, K, V, _ = rand_unit(84, n, d)
+    cls = np.zeros(n, dtype=np.uint8)
+    q, k, v, _ = _decode_inputs(85, S, d)
+    cn = np.zeros(S, dtype=np.uint8)
+    r_l = 0.2
+    w = 6
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, 0.0, 0.4, forced_policy=3,
+                      record_states=True)
+    assert res["profile"].window == w
+    assert list(res["init_pos"]) == list(range(n - w, n))
+    allK, allV = np.vstack([K, k]), np.vstack([V, v])
+    for t in range(S):
+        p = n + t
+        # held during the step: what the previous step kept (pos > p-1-w) plus the new token
+        held = list(range(p - w, p + 1))
+        lg = np.array([0.4 * q[t] @ allK[j] for j in held])
+        a = np.exp(lg - lg.max())
+        a /= a.sum()
+        assert np.allclose(res["outs"][t], a @ allV[held], atol=1e-13)
+        assert list(res["states"][t]) == list(range(p - w + 1, p + 1))
+
+
+def test_q0_decode_scores_closed_form():
+    """q = 0 at decode: a_j = 1/#held for every held token; scores follow exactly."""
+    n, d, S = 20, 4, 8
+    Q = np.zeros((n, d))
+    K = np.ones((n, d))
+    V = np.arange(n * d, dtype=np.float64).reshape(n, d)
+    cls = np.zeros(n, dtype=np.uint8)
+    cls[0] = 1
+    q = np.zeros((S, d))
+    k = np.ones((S, d))
+    v = np.ones((S, d))
+    cn = np.zeros(S, dtype=np.uint8)
+    r_f = 0.5
+    prof = fo.profile_unit(Q, K, cls, 0.5, 0.1, r_f, 1.0, forced_policy=2)
+    cache = fo.compact_unit(K, V, cls, prof)
+    assert list(cache.pos) == list(range(10))             # top 10 colsums = first 10 positions
+    H = [harmonic(i) for i in range(n + 1)]
+    score = {j: H[n] - H[j] for j in range(10)}
+    for t in range(S):
+        p = n + t
+        o = fo.decode_step(cache, q[t], k[t], v[t], 0, t, 0.1, r_f, 1.0)
+        held = sorted(score) + [p]
+        score[p] = Fraction(0)
+        for j in held:
+            score[j] += Fraction(1, len(held))
+        assert np.allclose(o, np.mean(np.vstack([V, v])[held], axis=0), atol=1e-12)
+        kf = (p + 1) // 2
+        ranked = sorted(held, key=lambda j: (-score[j], j))
+        keep = set(ranked[:kf]) | {0}
+        score = {j: s for j, s in score.items() if j in keep}
+        assert list(cache.pos) == sorted(keep)
+        assert np.allclose(cache.score, [float(score[j]) for j in sorted(keep)], atol=1e-13)
+
+
+@pytest.mark.parametrize("policy", [2, 3])
+def test_decode_set_equation_rederived_each_step(policy):
+    """Independent re-derivation with python sets/dicts (no shared helper): held and scores
+    after every step for the policies that contain `frequent`."""
+    n, d, S = 26, 8, 20
+    scale, r_l, r_f = 0.4, 0.2, 0.3
+    Q, K, V, cls = rand_unit(90 + policy, n, d, p_punct=0.15)
+    q, k, v, cn = _decode_inputs(95, S, d)
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale, forced_policy=policy,
+                      record_states=True)
+    prof = res["profile"]
+    w = max(1, math.floor(r_l * n))
+    allK, allV, allc = np.vstack([K, k]), np.vstack([V, v]), np.concatenate([cls, cn])
+    score = {int(j): float(prof.colsum[j]) for j in res["init_pos"]}
+    for t in range(S):
+        p = n + t
+        score[p] = 0.0
+        held = sorted(score)
+        lg = np.array([scale * q[t] @ allK[j] for j in held])
+        a = np.exp(lg - lg.max())
+        a /= a.sum()
+        assert np.allclose(res["outs"][t], a @ allV[held], atol=1e-12)
+        for j, aj in zip(held, a):
+            score[j] += aj
+        kf = math.floor(r_f * (p + 1))
+        ranked = sorted(held, key=lambda j: (-score[j], j))
+        keep = set(ranked[:kf]) | {j for j in held if allc[j] & 3}
+        if policy == 3:
+            keep |= {j for j in held if j > p - w}
+        score = {j: s for j, s in score.items() if j in keep}
+        assert list(res["states"][t]) == sorted(keep)
