@@ -260,6 +260,7 @@ def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, sc
     outs = np.zeros((S, d))
     lens = np.zeros(S, dtype=np.int64)
     states: List[np.ndarray] = []
+    score_states: List[np.ndarray] = []
     init_pos = cache.pos.copy()
     for t in range(S):
         outs[t] = decode_step(cache, q_steps[t], k_steps[t], v_steps[t], int(cls_steps[t]),
@@ -267,4 +268,6 @@ def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, sc
         lens[t] = cache.pos.size
         if record_states:
             states.append(cache.pos.copy())
-    return dict(profile=prof, init_pos=init_pos, outs=outs, lens=lens, states=states, cache=cache)
+            score_states.append(cache.score.copy())
+    return dict(profile=prof, init_pos=init_pos, outs=outs, lens=lens, states=states,
+                score_states=score_states, cache=cache)

@@ -1,0 +1,178 @@
+"""Thin Python binding of libfastgen.so (ctypes): argument marshalling only.
+
+Every step of the path runs inside the HIP library; PyTorch only supplies device memory and
+the stream. There is no fallback: if the library has not been built (``python -m
+paper_2310_01801_amd.build``) loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastgen.so")
+
+FG_OK, FG_EINVAL, FG_ENOMEM, FG_EHIP, FG_ESTATE, FG_ECAP = range(6)
+FG_F32, FG_BF16 = 0, 1
+STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_ECAP")
+
+EXPORTED = (
+    "fastgen_workspace_bytes", "fastgen_create", "fastgen_destroy", "fastgen_profile",
+    "fastgen_compact", "fastgen_decode_step", "fastgen_export_state", "fastgen_last_error",
+    "fastgen_version",
+)
+
+
+class FgConfig(ctypes.Structure):
+    _fields_ = [
+        ("num_units", ctypes.c_int32), ("num_seqs", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("dtype", ctypes.c_int32), ("prompt_len", ctypes.c_int32), ("max_new_tokens", ctypes.c_int32),
+        ("T", ctypes.c_double), ("r_l", ctypes.c_double), ("r_f", ctypes.c_double),
+        ("softmax_scale", ctypes.c_float), ("forced_policy", ctypes.c_int32),
+        ("cache_tokens", ctypes.c_int64),
+    ]
+
+
+class FastGenError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {message}")
+        self.status = status
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+def load_library() -> ctypes.CDLL:
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2310_01801_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, cp = ctypes.c_void_p, ctypes.POINTER(FgConfig)
+    lib.fastgen_workspace_bytes.restype = ctypes.c_size_t
+    lib.fastgen_workspace_bytes.argtypes = [cp]
+    lib.fastgen_create.restype = ctypes.c_int
+    lib.fastgen_create.argtypes = [cp, vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+    lib.fastgen_destroy.restype = ctypes.c_int
+    lib.fastgen_destroy.argtypes = [vp]
+    lib.fastgen_profile.restype = ctypes.c_int
+    lib.fastgen_profile.argtypes = [vp] * 9
+    lib.fastgen_compact.restype = ctypes.c_int
+    lib.fastgen_compact.argtypes = [vp] * 4
+    lib.fastgen_decode_step.restype = ctypes.c_int
+    lib.fastgen_decode_step.argtypes = [vp] * 7
+    lib.fastgen_export_state.restype = ctypes.c_int
+    lib.fastgen_export_state.argtypes = [vp] * 9
+    lib.fastgen_last_error.restype = ctypes.c_char_p
+    lib.fastgen_last_error.argtypes = [vp]
+    lib.fastgen_version.restype = ctypes.c_char_p
+    lib.fastgen_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_config(num_units: int, num_seqs: int, head_dim: int, dtype: torch.dtype, prompt_len: int,
+                max_new_tokens: int, T: float, r_l: float, r_f: float, softmax_scale: float = 0.0,
+                forced_policy: int = -1, cache_tokens: int = 0) -> FgConfig:
+    code = {torch.float32: FG_F32, torch.bfloat16: FG_BF16}[dtype]
+    return FgConfig(num_units, num_seqs, head_dim, code, prompt_len, max_new_tokens, T, r_l, r_f,
+                    softmax_scale, forced_policy, cache_tokens)
+
+
+def fastgen_workspace_bytes(cfg: FgConfig) -> int:
+    return int(load_library().fastgen_workspace_bytes(ctypes.byref(cfg)))
+
+
+class FastGen:
+    """One context over a torch-allocated workspace. Methods mirror the C entry points."""
+
+    def __init__(self, cfg: FgConfig, device: str = "cuda:0"):
+        self.lib = load_library()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        nbytes = fastgen_workspace_bytes(cfg)
+        if nbytes == 0:
+            raise FastGenError(FG_EINVAL, "invalid configuration")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._ctx = ctypes.c_void_p()
+        st = self.lib.fastgen_create(ctypes.byref(cfg), self.workspace.data_ptr(), nbytes,
+                                     ctypes.byref(self._ctx))
+        if st != FG_OK:
+            raise FastGenError(st, "fastgen_create failed")
+        self.tdtype = torch.float32 if cfg.dtype == FG_F32 else torch.bfloat16
+
+    def close(self) -> None:
+        if self._ctx:
+            self.lib.fastgen_destroy(self._ctx)
+            self._ctx = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int) -> None:
+        if st != FG_OK:
+            raise FastGenError(st, self.lib.fastgen_last_error(self._ctx).decode())
+
+    # -- stage 1
+    def fastgen_profile(self, Q: torch.Tensor, K: torch.Tensor, token_class: torch.Tensor,
+                        lse: Optional[torch.Tensor] = None
+                        ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+        U = self.cfg.num_units
+        policy = torch.empty(U, dtype=torch.int32, device=self.device)
+        recovery = torch.empty((U, 5), dtype=torch.float64, device=self.device)
+        kept = torch.empty((U, 5), dtype=torch.int32, device=self.device)
+        self._check(self.lib.fastgen_profile(self._ctx, _ptr(Q), _ptr(K), _ptr(token_class), _ptr(lse),
+                                             _ptr(policy), _ptr(recovery), _ptr(kept), _stream()))
+        return policy, recovery, kept
+
+    def fastgen_compact(self, K: torch.Tensor, V: torch.Tensor) -> None:
+        self._check(self.lib.fastgen_compact(self._ctx, _ptr(K), _ptr(V), _stream()))
+
+    # -- stage 2
+    def fastgen_decode_step(self, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                            class_new: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+        if out is None:
+            out = torch.empty((self.cfg.num_units, self.cfg.head_dim), dtype=self.tdtype, device=self.device)
+        self._check(self.lib.fastgen_decode_step(self._ctx, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                 _ptr(class_new), _ptr(out), _stream()))
+        return out
+
+    def fastgen_export_state(self, rows: bool = False) -> Dict[str, torch.Tensor]:
+        U, d = self.cfg.num_units, self.cfg.head_dim
+        lengths = torch.empty(U, dtype=torch.int32, device=self.device)
+        offsets = torch.empty(U + 1, dtype=torch.int64, device=self.device)
+        status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        # first the lengths, to size the packed outputs
+        self._check(self.lib.fastgen_export_state(self._ctx, _ptr(lengths), _ptr(offsets), None, None,
+                                                  None, None, _ptr(status), _stream()))
+        total = int(offsets[-1].item())
+        positions = torch.empty(max(total, 1), dtype=torch.int32, device=self.device)
+        scores = torch.empty(max(total, 1), dtype=torch.float64, device=self.device)
+        keys = values = None
+        if rows:
+            keys = torch.empty((max(total, 1), d), dtype=self.tdtype, device=self.device)
+            values = torch.empty_like(keys)
+        self._check(self.lib.fastgen_export_state(self._ctx, _ptr(lengths), _ptr(offsets), _ptr(positions),
+                                                  _ptr(scores), _ptr(keys), _ptr(values), _ptr(status),
+                                                  _stream()))
+        return dict(lengths=lengths, offsets=offsets, positions=positions[:total], scores=scores[:total],
+                    keys=None if keys is None else keys[:total],
+                    values=None if values is None else values[:total], status=status)

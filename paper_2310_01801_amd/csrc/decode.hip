@@ -1,0 +1,294 @@
+// One decode step over the ragged compressed caches (Alg. 2: attend with K^,V^ plus the new
+// token, then re-apply f with the head's policy; policies of Sec. 3.4).
+//
+//   fg_decode_partial_kernel  split-KV attention. The flat work list has one item per 256
+//       reserved slots of a unit (static after compaction); an item streams the K and V rows
+//       of its held slots with 16-byte-per-lane coalesced loads (a 256-byte bf16 row = 16
+//       lanes, 4 rows per wave load), keeps the scaled logits, and emits (max, sum, o) of its
+//       chunk. The item that owns the first free slot takes the new token from k_new/v_new
+//       and appends it to the cache on the way.
+//   fg_decode_finish_kernel   one workgroup per unit: merges the chunk partials into the
+//       attention output; adds this step's attention to the cumulative scores (policies with
+//       `frequent`); re-derives the kept set  special | punct | TopK(score, k_f(L)) | window
+//       and releases the evicted slots in place (holes below the new length are filled with
+//       the kept rows from above it).
+#include "fg_common.h"
+#include "fg_internal.h"
+#include "fg_select.h"
+
+namespace {
+
+constexpr int CH = FG_DECODE_CHUNK;
+
+template <int ESIZE>
+__device__ __forceinline__ void fg_unpack(const u32x4& v, float* f);
+template <>
+__device__ __forceinline__ void fg_unpack<2>(const u32x4& v, float* f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = fg_bf16_lo(v[i]);
+    f[2 * i + 1] = fg_bf16_hi(v[i]);
+  }
+}
+template <>
+__device__ __forceinline__ void fg_unpack<4>(const u32x4& v, float* f) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(v[i]);
+}
+
+template <int ESIZE, int D>
+__global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a) {
+  constexpr int RB = D * ESIZE;        // bytes per row
+  constexpr int LPR = RB / 16;         // lanes per row
+  constexpr int TPL = 64 / LPR;        // rows per wave load
+  constexpr int EPL = 16 / ESIZE;      // elements per lane
+  constexpr int ITERS = 64 / TPL;      // loads per wave for its 64 tokens
+  __shared__ float s_red[8];
+  __shared__ float s_o[4][D];
+
+  if (a.flags[0] != 0) return;
+  const int item = blockIdx.x;
+  if (item >= a.chunk_off[a.U]) return;
+  const int u = a.item_unit[item];
+  const int chunk = item - a.chunk_off[u];
+  const int Lold = a.len[u], L = Lold + 1;
+  const int start = chunk * CH;
+  if (start >= L) return;
+  if (L > a.cap[u]) {  // cannot happen while the host bounds the step count
+    if (threadIdx.x == 0) a.flags[0] = 1;
+    return;
+  }
+  const int cnt = min(CH, L - start);
+  const int64_t off = a.off[u];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane % LPR, sub = lane / LPR;
+  const float c = a.scale * FG_LOG2E;
+
+  const char* ck = static_cast<const char*>(a.ck);
+  const char* cv = static_cast<const char*>(a.cv);
+  const char* kn = static_cast<const char*>(a.k_new) + (size_t)u * RB;
+  const char* vn = static_cast<const char*>(a.v_new) + (size_t)u * RB;
+
+  float qv[EPL];
+  {
+    const u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(a.q) + (size_t)u * RB + g * 16);
+    fg_unpack<ESIZE>(t, qv);
+  }
+
+  u32x4 kv[ITERS], vv[ITERS];
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int tok = wave * 64 + it * TPL + sub;
+    const int slot = start + tok;
+    u32x4 kk = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
+    if (tok < cnt) {
+      if (slot == Lold) {  // the new token: read it from the step inputs and append it
+        kk = *reinterpret_cast<const u32x4*>(kn + g * 16);
+        vw = *reinterpret_cast<const u32x4*>(vn + g * 16);
+        *reinterpret_cast<u32x4*>(static_cast<char*>(a.ck) + (off + slot) * RB + g * 16) = kk;
+        *reinterpret_cast<u32x4*>(static_cast<char*>(a.cv) + (off + slot) * RB + g * 16) = vw;
+        if (g == 0) {
+          a.cpos[off + slot] = a.n + a.step;
+          a.ccls[off + slot] = a.class_new[u / a.units_per_seq];
+          a.cscore[off + slot] = 0.0;
+        }
+      } else {
+        kk = *reinterpret_cast<const u32x4*>(ck + (off + slot) * RB + g * 16);
+        vw = *reinterpret_cast<const u32x4*>(cv + (off + slot) * RB + g * 16);
+      }
+    }
+    kv[it] = kk;
+    vv[it] = vw;
+  }
+
+  // scaled logits (log2 domain): x = c * q.k, one value per token shared by its LPR lanes
+  float x[ITERS];
+  float mx = FG_NEG_BIG;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    float kf[EPL];
+    fg_unpack<ESIZE>(kv[it], kf);
+    float dot = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+#pragma unroll
+    for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
+    const int tok = wave * 64 + it * TPL + sub;
+    const bool ok = tok < cnt;
+    x[it] = ok ? dot * c : FG_NEG_BIG;
+    if (ok && g == 0) a.clogit[off + start + tok] = x[it];
+    mx = fmaxf(mx, x[it]);
+  }
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+
+  float lsum = 0.f;
+  float oacc[EPL];
+#pragma unroll
+  for (int e = 0; e < EPL; ++e) oacc[e] = 0.f;
+#pragma unroll
+  for (int it = 0; it < ITERS; ++it) {
+    const int tok = wave * 64 + it * TPL + sub;
+    const float p = (tok < cnt) ? fg_exp2(x[it] - M) : 0.f;
+    lsum += p;
+    float vf[EPL];
+    fg_unpack<ESIZE>(vv[it], vf);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) oacc[e] = fmaf(p, vf[e], oacc[e]);
+  }
+  // combine the row groups of the wave (lanes with equal g)
+#pragma unroll
+  for (int m = LPR; m < 64; m <<= 1) {
+    lsum += __shfl_xor(lsum, m, 64);
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) oacc[e] += __shfl_xor(oacc[e], m, 64);
+  }
+  if (sub == 0) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) s_o[wave][g * EPL + e] = oacc[e];
+  }
+  if (lane == 0) s_red[4 + wave] = lsum;
+  __syncthreads();
+  float* part = a.part + (size_t)item * (D + 2);
+  if (tid < D) part[2 + tid] = (s_o[0][tid] + s_o[1][tid]) + (s_o[2][tid] + s_o[3][tid]);
+  if (tid == 0) {
+    part[0] = M;
+    part[1] = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+  }
+}
+
+template <int ESIZE>
+__device__ __forceinline__ void fg_store_out(void* out, size_t idx, float v);
+template <>
+__device__ __forceinline__ void fg_store_out<2>(void* out, size_t idx, float v) {
+  static_cast<uint16_t*>(out)[idx] = (uint16_t)fg_f32_to_bf16_bits(v);
+}
+template <>
+__device__ __forceinline__ void fg_store_out<4>(void* out, size_t idx, float v) {
+  static_cast<float*>(out)[idx] = v;
+}
+
+template <int ESIZE, int D>
+__global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a) {
+  constexpr int RB = D * ESIZE, CPR = RB / 16;
+  __shared__ fg_select_smem sm;
+  __shared__ int ired[20];
+  if (a.flags[0] != 0) return;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int Lold = a.len[u], L = Lold + 1;
+  if (L > a.cap[u]) return;
+  const int nch = (L + CH - 1) / CH;
+  const float* part = a.part + (size_t)a.chunk_off[u] * (D + 2);
+  const int64_t off = a.off[u];
+
+  // ---- merge the chunk partials: o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M)
+  float M = FG_NEG_BIG;
+  for (int cix = 0; cix < nch; ++cix) M = fmaxf(M, part[(size_t)cix * (D + 2)]);
+  float Lsum = 0.f;
+  for (int cix = 0; cix < nch; ++cix)
+    Lsum += part[(size_t)cix * (D + 2) + 1] * fg_exp2(part[(size_t)cix * (D + 2)] - M);
+  const float inv = 1.0f / Lsum;
+  if (tid < D) {
+    float o = 0.f;
+    for (int cix = 0; cix < nch; ++cix)
+      o += part[(size_t)cix * (D + 2) + 2 + tid] * fg_exp2(part[(size_t)cix * (D + 2)] - M);
+    fg_store_out<ESIZE>(a.out, (size_t)u * D + tid, o * inv);
+  }
+
+  const int policy = a.policy[u];
+  if (policy >= 4) {
+    if (tid == 0) a.len[u] = L;
+    return;
+  }
+  const int p_new = a.n + a.step;
+  double* score = a.cscore + off;
+  const int32_t* pos = a.cpos + off;
+  const uint8_t* cls = a.ccls + off;
+
+  fg_topk tk;
+  tk.mode = 0; tk.thr = 0; tk.pthr = 0;
+  if (policy >= 2) {
+    // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
+    for (int j = tid; j < L; j += 256) {
+      const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
+      score[j] += (double)aj;
+    }
+    __syncthreads();
+    const int k_f = fg_budget(a.r_f, p_new + 1);
+    tk = fg_select_topk([&](int j) { return score[j]; }, [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
+  }
+  auto kept = [&](int j) -> bool {
+    const int cbits = cls[j];
+    bool k = (cbits & FG_CLASS_SPECIAL) != 0;
+    if (policy >= 1) k = k || (cbits & FG_CLASS_PUNCT) != 0;
+    if (policy >= 2) k = k || fg_in_topk(tk, score[j], (uint32_t)pos[j]);
+    if (policy >= 3) k = k || (pos[j] > p_new - a.w);
+    return k;
+  };
+  int mine = 0;
+  for (int j = tid; j < L; j += 256) mine += kept(j) ? 1 : 0;
+  const int new_len = fg_block_sum_i32(mine, ired);
+  if (new_len == L) {
+    if (tid == 0) a.len[u] = L;
+    return;
+  }
+
+  // ---- in-place release: i-th hole (evicted slot below new_len) <- i-th kept slot above it
+  int* scratch = reinterpret_cast<int*>(a.clogit + off);  // logits are dead from here on
+  const int cap = a.cap[u];
+  __syncthreads();
+  int run_h = 0, run_m = 0;
+  for (int base = 0; base < L; base += 256) {
+    const int j = base + tid;
+    int is_h = 0, is_m = 0;
+    if (j < L) {
+      const bool k = kept(j);
+      is_h = (j < new_len && !k) ? 1 : 0;
+      is_m = (j >= new_len && k) ? 1 : 0;
+    }
+    int tot_h, tot_m;
+    const int ex_h = fg_block_exscan_i32(is_h, ired, &tot_h);
+    __syncthreads();
+    const int ex_m = fg_block_exscan_i32(is_m, ired, &tot_m);
+    if (is_h) scratch[run_h + ex_h] = j;
+    if (is_m) scratch[cap - 1 - (run_m + ex_m)] = j;
+    run_h += tot_h;
+    run_m += tot_m;
+    __syncthreads();
+  }
+  const int moves = run_h;  // == run_m
+  char* ck = static_cast<char*>(a.ck) + off * RB;
+  char* cv = static_cast<char*>(a.cv) + off * RB;
+  for (int q = tid; q < moves * CPR; q += 256) {
+    const int i = q / CPR, ch = q % CPR;
+    const int dst = scratch[i], src = scratch[cap - 1 - i];
+    *reinterpret_cast<u32x4*>(ck + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(ck + (size_t)src * RB + ch * 16);
+    *reinterpret_cast<u32x4*>(cv + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(cv + (size_t)src * RB + ch * 16);
+  }
+  // the kept() predicate reads score/pos/cls: move them only after every thread is done with it
+  __syncthreads();
+  for (int i = tid; i < moves; i += 256) {
+    const int dst = scratch[i], src = scratch[cap - 1 - i];
+    score[dst] = score[src];
+    a.cpos[off + dst] = pos[src];
+    a.ccls[off + dst] = cls[src];
+  }
+  if (tid == 0) a.len[u] = new_len;
+}
+
+template <int ESIZE, int D>
+hipError_t launch(const fg_decode_args& a, hipStream_t s) {
+  hipLaunchKernelGGL((fg_decode_partial_kernel<ESIZE, D>), dim3((unsigned)a.max_chunks), dim3(256), 0, s, a);
+  hipLaunchKernelGGL((fg_decode_finish_kernel<ESIZE, D>), dim3((unsigned)a.U), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t fg_launch_decode(const fg_decode_args& a, hipStream_t s) {
+  if (a.dtype == FG_BF16) return a.d == 128 ? launch<2, 128>(a, s) : launch<2, 64>(a, s);
+  return a.d == 128 ? launch<4, 128>(a, s) : launch<4, 64>(a, s);
+}

@@ -1,0 +1,272 @@
+// C ABI of the FastGen hot path: argument validation, workspace carve-up, launch order.
+// See include/fastgen.h for the contract of every entry point.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "fg_common.h"
+#include "fg_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool config_ok(const fg_config* c, char* why, size_t why_len) {
+#define FG_REQUIRE(cond, msg)                 \
+  if (!(cond)) {                              \
+    if (why) snprintf(why, why_len, "%s", msg); \
+    return false;                             \
+  }
+  FG_REQUIRE(c != nullptr, "config is NULL");
+  FG_REQUIRE(c->num_units > 0 && c->num_units <= (1 << 24), "num_units out of range");
+  FG_REQUIRE(c->num_seqs > 0 && c->num_units % c->num_seqs == 0, "num_seqs must divide num_units");
+  FG_REQUIRE(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
+  FG_REQUIRE(c->dtype == FG_F32 || c->dtype == FG_BF16, "dtype must be FG_F32 or FG_BF16");
+  FG_REQUIRE(c->prompt_len >= 1 && c->prompt_len <= (1 << 20), "prompt_len out of range");
+  FG_REQUIRE(c->max_new_tokens >= 0 && c->max_new_tokens <= (1 << 20), "max_new_tokens out of range");
+  FG_REQUIRE(c->T > 0.0 && c->T <= 1.0, "T must be in (0, 1]");
+  FG_REQUIRE(c->r_l >= 0.0 && c->r_l <= 1.0, "r_l must be in [0, 1]");
+  FG_REQUIRE(c->r_f >= 0.0 && c->r_f <= 1.0, "r_f must be in [0, 1]");
+  FG_REQUIRE(c->softmax_scale >= 0.f && isfinite(c->softmax_scale), "softmax_scale must be >= 0");
+  FG_REQUIRE(c->forced_policy >= -1 && c->forced_policy <= 4, "forced_policy must be -1..4");
+  FG_REQUIRE(c->cache_tokens >= 0, "cache_tokens must be >= 0");
+#undef FG_REQUIRE
+  return true;
+}
+
+fg_layout make_layout(const fg_config& c) {
+  fg_layout L;
+  memset(&L, 0, sizeof(L));
+  const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len, d = (size_t)c.head_dim;
+  const size_t e = c.dtype == FG_BF16 ? 2 : 4;
+  const size_t full = n + (size_t)c.max_new_tokens;
+  const size_t pool = c.cache_tokens > 0 ? (size_t)c.cache_tokens : U * full;
+  L.pool_tokens = (int64_t)pool;
+  L.max_chunks = (int64_t)(pool / FG_DECODE_CHUNK + U);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  L.lse2 = take(U * n * 4);
+  L.colsum = take(U * n * 8);
+  L.bandcol = take(U * n * 8);
+  L.keep = take(U * n);
+  L.slot = take(U * n * 4);
+  L.policy = take(U * 4);
+  L.recov = take(U * 5 * 8);
+  L.kcount = take(U * 5 * 4);
+  L.cap = take(U * 4);
+  L.off = take((U + 1) * 8);
+  L.len = take(U * 4);
+  L.flags = take(8 * 4);
+  L.ck = take(pool * d * e);
+  L.cv = take(pool * d * e);
+  L.cscore = take(pool * 8);
+  L.cpos = take(pool * 4);
+  L.ccls = take(pool);
+  L.clogit = take(pool * 4);
+  L.chunk_off = take((U + 1) * 4);
+  L.item_unit = take((size_t)L.max_chunks * 4);
+  L.part = take((size_t)L.max_chunks * (d + 2) * 4);
+  L.total = o;
+  return L;
+}
+
+fg_status fail(fastgen_ctx* ctx, fg_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+fg_status hip_fail(fastgen_ctx* ctx, hipError_t e, const char* where) {
+  return fail(ctx, FG_EHIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+template <class T>
+T* at(fastgen_ctx* ctx, size_t off) { return reinterpret_cast<T*>(ctx->ws + off); }
+
+}  // namespace
+
+extern "C" {
+
+size_t fastgen_workspace_bytes(const fg_config* cfg) {
+  if (!config_ok(cfg, nullptr, 0)) return 0;
+  return make_layout(*cfg).total;
+}
+
+fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fastgen_ctx** out) {
+  if (!out) return FG_EINVAL;
+  *out = nullptr;
+  char why[128];
+  if (!config_ok(cfg, why, sizeof(why))) return FG_EINVAL;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0) return FG_EINVAL;
+  fg_layout lay = make_layout(*cfg);
+  if (bytes < lay.total) return FG_ENOMEM;
+  fastgen_ctx* ctx = new (std::nothrow) fastgen_ctx;
+  if (!ctx) return FG_ENOMEM;
+  memset(ctx, 0, sizeof(*ctx));
+  ctx->cfg = *cfg;
+  ctx->lay = lay;
+  ctx->ws = static_cast<char*>(workspace);
+  ctx->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
+  const int w = fg_budget(cfg->r_l, cfg->prompt_len);
+  ctx->w = w < 1 ? 1 : w;
+  ctx->stage = 0;
+  ctx->steps_done = 0;
+  ctx->err[0] = '\0';
+  *out = ctx;
+  return FG_OK;
+}
+
+fg_status fastgen_destroy(fastgen_ctx* ctx) {
+  delete ctx;
+  return FG_OK;
+}
+
+fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const uint8_t* token_class,
+                          const float* lse_opt, int32_t* policy, double* recovery,
+                          int32_t* kept_count, void* stream) {
+  if (!ctx) return FG_EINVAL;
+  if (!Q || !K || !token_class) return fail(ctx, FG_EINVAL, "fastgen_profile: Q, K and token_class are required");
+  if (!aligned16(Q) || !aligned16(K)) return fail(ctx, FG_EINVAL, "fastgen_profile: Q and K must be 16-byte aligned");
+  if (ctx->stage != 0) return fail(ctx, FG_ESTATE, "fastgen_profile: context already profiled");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const fg_config& c = ctx->cfg;
+  const fg_layout& L = ctx->lay;
+
+  fg_profile_args pa;
+  pa.Q = Q; pa.K = K;
+  pa.lse2 = at<float>(ctx, L.lse2);
+  pa.colsum = at<double>(ctx, L.colsum);
+  pa.bandcol = at<double>(ctx, L.bandcol);
+  pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w;
+  pa.scale = ctx->scale;
+  pa.run_pass1 = (lse_opt == nullptr);
+  hipError_t e;
+  if (lse_opt) {
+    e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * c.prompt_len, s);
+    if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(lse)");
+  }
+  e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, s) : fg_launch_profile_f32(pa, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(attention sweeps)");
+
+  fg_select_args sa;
+  sa.colsum = pa.colsum; sa.bandcol = pa.bandcol; sa.token_class = token_class;
+  sa.keep = at<uint8_t>(ctx, L.keep); sa.slot = at<int32_t>(ctx, L.slot);
+  sa.policy = at<int32_t>(ctx, L.policy); sa.recov = at<double>(ctx, L.recov);
+  sa.kcount = at<int32_t>(ctx, L.kcount); sa.cap = at<int32_t>(ctx, L.cap);
+  sa.len = at<int32_t>(ctx, L.len);
+  sa.policy_out = policy; sa.recov_out = recovery; sa.kcount_out = kept_count;
+  sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
+  sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f;
+  sa.forced_policy = c.forced_policy;
+  e = fg_launch_select(sa, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(select)");
+  ctx->stage = 1;
+  return FG_OK;
+}
+
+fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* stream) {
+  if (!ctx) return FG_EINVAL;
+  if (!K || !V) return fail(ctx, FG_EINVAL, "fastgen_compact: K and V are required");
+  if (!aligned16(K) || !aligned16(V)) return fail(ctx, FG_EINVAL, "fastgen_compact: K and V must be 16-byte aligned");
+  if (ctx->stage != 1) return fail(ctx, FG_ESTATE, "fastgen_compact: needs fastgen_profile first (once)");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const fg_config& c = ctx->cfg;
+  const fg_layout& L = ctx->lay;
+  hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int64_t>(ctx, L.off),
+                                   at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
+                                   at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
+                                   L.max_chunks, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(offsets)");
+  fg_compact_args ca;
+  ca.K = K; ca.V = V;
+  ca.token_class = nullptr;  // class bits travel inside the keep bytes
+  ca.colsum = at<double>(ctx, L.colsum); ca.keep = at<uint8_t>(ctx, L.keep);
+  ca.slot = at<int32_t>(ctx, L.slot); ca.cap = at<int32_t>(ctx, L.cap);
+  ca.off = at<int64_t>(ctx, L.off); ca.len = at<int32_t>(ctx, L.len);
+  ca.flags = at<int32_t>(ctx, L.flags);
+  ca.ck = at<void>(ctx, L.ck); ca.cv = at<void>(ctx, L.cv);
+  ca.cscore = at<double>(ctx, L.cscore); ca.cpos = at<int32_t>(ctx, L.cpos);
+  ca.ccls = at<uint8_t>(ctx, L.ccls);
+  ca.U = c.num_units; ca.n = c.prompt_len; ca.d = c.head_dim;
+  ca.esize = c.dtype == FG_BF16 ? 2 : 4;
+  ca.units_per_seq = c.num_units / c.num_seqs;
+  ca.pool_tokens = L.pool_tokens;
+  e = fg_launch_compact(ca, s);
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(gather)");
+  ctx->stage = 2;
+  ctx->steps_done = 0;
+  return FG_OK;
+}
+
+fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                              const uint8_t* class_new, void* out, void* stream) {
+  if (!ctx) return FG_EINVAL;
+  if (!q || !k_new || !v_new || !class_new || !out)
+    return fail(ctx, FG_EINVAL, "fastgen_decode_step: q, k_new, v_new, class_new and out are required");
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out))
+    return fail(ctx, FG_EINVAL, "fastgen_decode_step: q, k_new, v_new, out must be 16-byte aligned");
+  if (ctx->stage != 2) return fail(ctx, FG_ESTATE, "fastgen_decode_step: needs fastgen_compact first");
+  const fg_config& c = ctx->cfg;
+  if (ctx->steps_done >= c.max_new_tokens)
+    return fail(ctx, FG_ECAP, "fastgen_decode_step: max_new_tokens (%d) steps already done", c.max_new_tokens);
+  const fg_layout& L = ctx->lay;
+  fg_decode_args da;
+  da.q = q; da.k_new = k_new; da.v_new = v_new; da.class_new = class_new; da.out = out;
+  da.policy = at<int32_t>(ctx, L.policy); da.cap = at<int32_t>(ctx, L.cap);
+  da.off = at<int64_t>(ctx, L.off); da.len = at<int32_t>(ctx, L.len);
+  da.flags = at<int32_t>(ctx, L.flags);
+  da.ck = at<void>(ctx, L.ck); da.cv = at<void>(ctx, L.cv);
+  da.cscore = at<double>(ctx, L.cscore); da.cpos = at<int32_t>(ctx, L.cpos);
+  da.ccls = at<uint8_t>(ctx, L.ccls); da.clogit = at<float>(ctx, L.clogit);
+  da.chunk_off = at<int32_t>(ctx, L.chunk_off); da.item_unit = at<int32_t>(ctx, L.item_unit);
+  da.part = at<float>(ctx, L.part);
+  da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;
+  da.units_per_seq = c.num_units / c.num_seqs; da.w = ctx->w; da.step = ctx->steps_done;
+  da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks;
+  hipError_t e = fg_launch_decode(da, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step");
+  ctx->steps_done += 1;
+  return FG_OK;
+}
+
+fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offsets, int32_t* positions,
+                               double* scores, void* keys, void* values, int32_t* status,
+                               void* stream) {
+  if (!ctx) return FG_EINVAL;
+  if (ctx->stage != 2) return fail(ctx, FG_ESTATE, "fastgen_export_state: needs fastgen_compact first");
+  if ((positions || scores || keys || values) && !offsets)
+    return fail(ctx, FG_EINVAL, "fastgen_export_state: packed outputs need `offsets`");
+  const fg_config& c = ctx->cfg;
+  const fg_layout& L = ctx->lay;
+  if ((size_t)(c.prompt_len + c.max_new_tokens) > (size_t)200000)
+    return fail(ctx, FG_EINVAL, "fastgen_export_state: prompt_len + max_new_tokens too large for the read-back kernel");
+  fg_export_args ea;
+  ea.off = at<int64_t>(ctx, L.off); ea.len = at<int32_t>(ctx, L.len);
+  ea.flags = at<int32_t>(ctx, L.flags);
+  ea.ck = at<void>(ctx, L.ck); ea.cv = at<void>(ctx, L.cv);
+  ea.cscore = at<double>(ctx, L.cscore); ea.cpos = at<int32_t>(ctx, L.cpos);
+  ea.lengths = lengths; ea.offsets = offsets; ea.positions = positions; ea.scores = scores;
+  ea.keys = keys; ea.values = values; ea.status = status;
+  ea.U = c.num_units; ea.d = c.head_dim; ea.esize = c.dtype == FG_BF16 ? 2 : 4;
+  ea.max_pos = c.prompt_len + c.max_new_tokens;
+  hipError_t e = fg_launch_export(ea, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_export_state");
+  return FG_OK;
+}
+
+const char* fastgen_last_error(const fastgen_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+const char* fastgen_version(void) { return "fastgen-mi355x 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,90 @@
+// Shared device-side helpers of the FastGen HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define FG_WAVE 64
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define FG_LOG2E 1.4426950408889634f
+
+// a finite stand-in for -infinity that survives (x - x) without producing NaN
+#define FG_NEG_BIG (-1.0e30f)
+
+__device__ __forceinline__ float fg_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ float fg_bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float fg_bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// round-to-nearest-even float -> bf16 bits (inputs are finite here)
+__device__ __forceinline__ uint32_t fg_f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ __forceinline__ double fg_shfl_xor_f64(double v, int mask) {
+  int lo = __double2loint(v), hi = __double2hiint(v);
+  lo = __shfl_xor(lo, mask, 64);
+  hi = __shfl_xor(hi, mask, 64);
+  return __hiloint2double(hi, lo);
+}
+
+// Deterministic block-wide sums (fixed tree order). `red` is LDS scratch with one slot per
+// wave; every thread of the block must call. All threads receive the total.
+__device__ __forceinline__ double fg_block_sum_f64(double v, double* red) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += fg_shfl_xor_f64(v, m);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+__device__ __forceinline__ int fg_block_sum_i32(int v, int* red) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  int t = 0;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+// Block-wide exclusive prefix sum of one int per thread (blockDim.x <= 1024, multiple of
+// 64). `red` needs 17 ints. Returns the exclusive prefix; *total receives the block sum.
+__device__ __forceinline__ int fg_block_exscan_i32(int v, int* red, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) red[wave] = inc;
+  __syncthreads();
+  int base = 0, tot = 0;
+  for (int i = 0; i < nw; ++i) {
+    int c = red[i];
+    if (i < wave) base += c;
+    tot += c;
+  }
+  *total = tot;
+  return base + inc - v;
+}
+
+// floor(r * L) in IEEE double: the budget rule of the frequent / local policies.
+__device__ __host__ __forceinline__ int fg_budget(double r, int L) {
+  double x = r * (double)L;
+  return (int)floor(x);
+}

@@ -1,0 +1,112 @@
+// Host-side plumbing shared by the translation units of the FastGen HIP library:
+// the context, the workspace carve-up and the kernel launchers. Not part of the ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fastgen.h"
+
+// ---------------------------------------------------------------- workspace layout
+// Every region starts on a 256-byte boundary. Offsets are in bytes from the workspace base.
+struct fg_layout {
+  // profiling scratch
+  size_t lse2;      // [U, n] float   row log2-sum-exp2 of the scaled logits
+  size_t colsum;    // [U, n] double  cumulative attention score of every prompt token
+  size_t bandcol;   // [U, n] double  the part of colsum inside the local band
+  size_t keep;      // [U, n] uint8   0 = dropped, else 4 | class bits of the kept token
+  size_t slot;      // [U, n] int32   exclusive prefix sum of keep (slot in the cache)
+  // per-unit results and cache bookkeeping
+  size_t policy;    // [U] int32
+  size_t recov;     // [U, 5] double
+  size_t kcount;    // [U, 5] int32
+  size_t cap;       // [U] int32      slots reserved for the unit
+  size_t off;       // [U + 1] int64  first slot of each unit in the pool
+  size_t len;       // [U] int32      tokens held
+  size_t flags;     // [8] int32      [0] pool overflow, [1] decode steps done
+  // ragged cache pool (pool_tokens slots)
+  size_t ck;        // [pool, d] dtype
+  size_t cv;        // [pool, d] dtype
+  size_t cscore;    // [pool] double
+  size_t cpos;      // [pool] int32
+  size_t ccls;      // [pool] uint8
+  size_t clogit;    // [pool] float   this step's scaled logit of every held token
+  // decode scratch
+  size_t chunk_off; // [U + 1] int32  first chunk of each unit in the flat work list
+  size_t item_unit; // [max_chunks] int32  unit of every work item (-1: unused)
+  size_t part;      // [max_chunks, d + 2] float  split-KV partial (max, sum, o)
+  size_t total;
+  int64_t pool_tokens;
+  int64_t max_chunks;
+};
+
+struct fastgen_ctx {
+  fg_config cfg;
+  fg_layout lay;
+  char* ws;
+  float scale;
+  int w;            // local window
+  int stage;        // 0 created, 1 profiled, 2 compacted / decoding
+  int steps_done;
+  char err[256];
+};
+
+constexpr int FG_DECODE_CHUNK = 256;  // tokens per split-KV work item
+
+// ---------------------------------------------------------------- launch arguments
+struct fg_profile_args {
+  const void* Q; const void* K;
+  float* lse2; double* colsum; double* bandcol;
+  int U, n, d, w;
+  float scale;
+  bool run_pass1;
+};
+
+struct fg_select_args {
+  const double* colsum; const double* bandcol; const uint8_t* token_class;  // [B, n]
+  uint8_t* keep; int32_t* slot;
+  int32_t* policy; double* recov; int32_t* kcount; int32_t* cap; int32_t* len;
+  int32_t* policy_out; double* recov_out; int32_t* kcount_out;  // optional caller copies
+  int U, n, units_per_seq, w, S;
+  double T, r_f;
+  int forced_policy;
+};
+
+struct fg_compact_args {
+  const void* K; const void* V;
+  const uint8_t* token_class; const double* colsum; const uint8_t* keep; const int32_t* slot;
+  const int32_t* cap; int64_t* off; const int32_t* len; int32_t* flags;
+  void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls;
+  int U, n, d, esize, units_per_seq;
+  int64_t pool_tokens;
+};
+
+struct fg_decode_args {
+  const void* q; const void* k_new; const void* v_new; const uint8_t* class_new; void* out;
+  const int32_t* policy; const int32_t* cap; const int64_t* off; int32_t* len; int32_t* flags;
+  void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; float* clogit;
+  const int32_t* chunk_off; const int32_t* item_unit; float* part;
+  int U, n, d, dtype, units_per_seq, w, step;
+  double r_f;
+  float scale;
+  int64_t max_chunks;
+};
+
+struct fg_export_args {
+  const int64_t* off; const int32_t* len; const int32_t* flags;
+  const void* ck; const void* cv; const double* cscore; const int32_t* cpos;
+  int32_t* lengths; int64_t* offsets; int32_t* positions; double* scores; void* keys; void* values;
+  int32_t* status;
+  int U, d, esize, max_pos;  // max_pos = n + S
+};
+
+hipError_t fg_launch_profile_bf16(const fg_profile_args&, hipStream_t);
+hipError_t fg_launch_profile_f32(const fg_profile_args&, hipStream_t);
+hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t);
+hipError_t fg_launch_select(const fg_select_args&, hipStream_t);
+hipError_t fg_launch_compact(const fg_compact_args&, hipStream_t);
+hipError_t fg_launch_offsets(const int32_t* cap, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
+                             int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
+                             hipStream_t);
+hipError_t fg_launch_decode(const fg_decode_args&, hipStream_t);
+hipError_t fg_launch_export(const fg_export_args&, hipStream_t);

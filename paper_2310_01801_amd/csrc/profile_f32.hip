@@ -1,0 +1,114 @@
+// Prompt-time attention profiling for float32 inputs (Alg. 1: A = softmax(Q K^T); Sec. 3.4
+// cumulative attention score). Same two sweeps and the same outputs as the bf16 matrix-core
+// kernel, on the vector ALU: this is the path of the small float32 correctness workload,
+// not a throughput path. One thread owns one query row (pass 1) or one key column (pass 2)
+// with its vector in registers; the other matrix is streamed through LDS in tiles of 32.
+#include "fg_common.h"
+#include "fg_internal.h"
+
+namespace {
+
+constexpr int kTile = 32;
+
+template <int D, int PASS>
+__global__ __launch_bounds__(256) void fg_profile_f32_kernel(
+    const float* __restrict__ Q, const float* __restrict__ K, float* __restrict__ lse2,
+    double* __restrict__ colsum, double* __restrict__ bandcol, int n, int w, float c, int nblk) {
+  __shared__ __attribute__((aligned(16))) float tile[kTile][D];
+  __shared__ float lse_t[kTile];
+
+  const int unit = blockIdx.x / nblk, tid = threadIdx.x;
+  const int WG0 = (blockIdx.x % nblk) * 256;
+  const int own = WG0 + tid;
+  const size_t base = (size_t)unit * (size_t)n * D;
+  const float* own_mat = (PASS == 1 ? Q : K) + base;
+  const float* str_mat = (PASS == 1 ? K : Q) + base;
+
+  float o[D];
+#pragma unroll
+  for (int k = 0; k < D; k += 4) {
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (own < n) v = *reinterpret_cast<const f32x4*>(own_mat + (size_t)own * D + k);
+    o[k] = v[0]; o[k + 1] = v[1]; o[k + 2] = v[2]; o[k + 3] = v[3];
+  }
+
+  int t_begin, t_end;
+  if (PASS == 1) { t_begin = 0; t_end = (min(n, WG0 + 256) + kTile - 1) / kTile; }
+  else { t_begin = WG0 / kTile; t_end = (n + kTile - 1) / kTile; }
+
+  float m_run = FG_NEG_BIG;
+  double l_run = 0.0, col_acc = 0.0, band_acc = 0.0;
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int t0 = t * kTile;
+    __syncthreads();
+    for (int q = tid; q < kTile * (D / 4); q += 256) {
+      const int item = q / (D / 4), ch = q % (D / 4);
+      f32x4 v = {0.f, 0.f, 0.f, 0.f};
+      if (t0 + item < n) v = *reinterpret_cast<const f32x4*>(str_mat + (size_t)(t0 + item) * D + ch * 4);
+      *reinterpret_cast<f32x4*>(&tile[item][ch * 4]) = v;
+    }
+    if (PASS == 2 && tid < kTile) lse_t[tid] = (t0 + tid < n) ? lse2[(size_t)unit * n + t0 + tid] : 0.f;
+    __syncthreads();
+    if (own >= n) continue;
+    for (int it = 0; it < kTile; ++it) {
+      const int s_idx = t0 + it;
+      if (s_idx >= n) break;
+      if (PASS == 1 && s_idx > own) break;   // causal: column <= row
+      if (PASS == 2 && s_idx < own) continue;  // causal: row >= column
+      float dot = 0.f;
+#pragma unroll
+      for (int k = 0; k < D; ++k) dot = fmaf(o[k], tile[it][k], dot);
+      const float x = dot * c;
+      if (PASS == 1) {
+        const float m_new = fmaxf(m_run, x);
+        l_run = l_run * (double)fg_exp2(m_run - m_new) + (double)fg_exp2(x - m_new);
+        m_run = m_new;
+      } else {
+        const float p = fg_exp2(x - lse_t[it]);
+        col_acc += (double)p;
+        if (s_idx - own < w) band_acc += (double)p;
+      }
+    }
+  }
+  if (own < n) {
+    if (PASS == 1) lse2[(size_t)unit * n + own] = m_run + (float)log2(l_run);
+    else {
+      colsum[(size_t)unit * n + own] = col_acc;
+      bandcol[(size_t)unit * n + own] = band_acc;
+    }
+  }
+}
+
+template <int D>
+hipError_t launch(const fg_profile_args& a, hipStream_t s) {
+  const int nblk = (a.n + 255) / 256;
+  const dim3 grid((unsigned)((size_t)nblk * a.U)), block(256);
+  const float c = a.scale * FG_LOG2E;
+  const float* Q = static_cast<const float*>(a.Q);
+  const float* K = static_cast<const float*>(a.K);
+  if (a.run_pass1)
+    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                       a.bandcol, a.n, a.w, c, nblk);
+  hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                     a.bandcol, a.n, a.w, c, nblk);
+  return hipGetLastError();
+}
+
+__global__ void fg_lse_to_log2_kernel(const float* __restrict__ in, float* __restrict__ out, size_t count) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < count) out[i] = in[i] * FG_LOG2E;
+}
+
+}  // namespace
+
+hipError_t fg_launch_profile_f32(const fg_profile_args& a, hipStream_t s) {
+  if (a.d == 128) return launch<128>(a, s);
+  return launch<64>(a, s);
+}
+
+hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t s) {
+  const unsigned blocks = (unsigned)((count + 255) / 256);
+  hipLaunchKernelGGL(fg_lse_to_log2_kernel, dim3(blocks), dim3(256), 0, s, lse_nat, lse2, count);
+  return hipGetLastError();
+}

@@ -1,0 +1,285 @@
+// Prompt-time attention profiling on the bf16 matrix cores (Alg. 1: A = softmax(Q K^T);
+// Sec. 3.4: cumulative attention score per token; Sec. 3.3 Eq. 1: recovery of a policy).
+//
+// The attention map is never stored. Two sweeps over the causal half of Q K^T:
+//   PASS 1  row log-sum-exp        lse2_i  = log2 sum_{j<=i} 2^(c * q_i.k_j),  c = scale*log2(e)
+//   PASS 2  column reductions      colsum_j  = sum_{i>=j}            2^(c * q_i.k_j - lse2_i)
+//                                  bandcol_j = sum_{i=j}^{j+w-1}     (same terms)
+// colsum is the "cumulative sum of attention score" of token j (frequent policy and every
+// static policy's recovery); bandcol is what the local policy recovers of column j.
+//
+// Both sweeps use one structure. A workgroup of 4 waves owns 256 consecutive "owner" items
+// (query rows in pass 1, key columns in pass 2), 64 per wave, held in registers as the B
+// operand of v_mfma_f32_32x32x16_bf16 so that the owner index is the lane index (n = lane%32).
+// The other matrix is streamed in tiles of 32 items through double-buffered LDS and read as
+// the A operand. Each lane therefore keeps its owner's running statistics privately:
+// (max, sum) of its row in pass 1, the column sums in pass 2, and only the two half-waves
+// are merged at the end. Reductions run in a fixed order: results are deterministic.
+#include "fg_common.h"
+#include "fg_internal.h"
+
+namespace {
+
+constexpr int kOwnPerWave = 64;
+constexpr int kOwnPerBlock = 256;
+constexpr int kTile = 32;
+
+template <int D>
+struct Lds {
+  static constexpr int kRowBytes = D * 2 + 16;  // +16: consecutive rows land on different banks
+  static constexpr int kTileBytes = kTile * kRowBytes;
+};
+
+template <int D, int PASS>
+__global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
+    const __bf16* __restrict__ Q, const __bf16* __restrict__ K, float* __restrict__ lse2,
+    double* __restrict__ colsum, double* __restrict__ bandcol, int U, int n, int w, float c,
+    int nblk) {
+  constexpr int KK = D / 16;
+  constexpr int RS = Lds<D>::kRowBytes;
+  constexpr int CHUNKS_PER_ROW = D / 8;                    // 16-byte chunks per item
+  constexpr int LOADS = (kTile * CHUNKS_PER_ROW) / 256;    // per thread per tile (2 or 1)
+  static_assert(LOADS >= 1, "tile too small");
+
+  __shared__ __attribute__((aligned(16))) unsigned char tile_lds[2][Lds<D>::kTileBytes];
+  __shared__ __attribute__((aligned(16))) float lse_lds[2][kTile];
+
+  // ---- which (unit, owner block): units of one XCD walk one unit's blocks back to back
+  const int idx = blockIdx.x;
+  const int xcd = idx & 7, rest = idx >> 3;
+  const int blk_ord = rest % nblk;
+  const int unit = (rest / nblk) * 8 + xcd;
+  if (unit >= U) return;
+  const int blk = (PASS == 1) ? (nblk - 1 - blk_ord) : blk_ord;  // heaviest first
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const size_t base = (size_t)unit * (size_t)n * D;
+  const __bf16* own_mat = (PASS == 1 ? Q : K) + base;
+  const __bf16* str_mat = (PASS == 1 ? K : Q) + base;
+  const float* lse_row = lse2 + (size_t)unit * n;
+
+  const int WG0 = blk * kOwnPerBlock;       // first owner item of the workgroup
+  const int O0 = WG0 + wave * kOwnPerWave;  // first owner item of the wave
+
+  // ---- owner fragments (B operand): item O0 + 32 f + ln, k-chunk lh*8 + 16 kk
+  bf16x8 own[2][KK];
+#pragma unroll
+  for (int f = 0; f < 2; ++f) {
+    const int item = O0 + 32 * f + ln;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (item < n) v = *reinterpret_cast<const u32x4*>(own_mat + (size_t)item * D + lh * 8 + 16 * kk);
+      own[f][kk] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  // ---- streamed tile range
+  int t_begin, t_end;  // in tiles of 32
+  if (PASS == 1) {
+    t_begin = 0;
+    t_end = (min(n, WG0 + kOwnPerBlock) + kTile - 1) / kTile;
+  } else {
+    t_begin = WG0 / kTile;
+    t_end = (n + kTile - 1) / kTile;
+  }
+
+  u32x4 stage[LOADS];
+  float stage_lse = 0.f;
+  auto gload = [&](int t) {
+    const int t0 = t * kTile;
+#pragma unroll
+    for (int r = 0; r < LOADS; ++r) {
+      const int q = tid + 256 * r;
+      const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (t0 + item < n) v = *reinterpret_cast<const u32x4*>(str_mat + (size_t)(t0 + item) * D + ch * 8);
+      stage[r] = v;
+    }
+    if (PASS == 2 && tid < kTile) stage_lse = (t0 + tid < n) ? lse_row[t0 + tid] : 0.f;
+  };
+  auto lstore = [&](int buf) {
+#pragma unroll
+    for (int r = 0; r < LOADS; ++r) {
+      const int q = tid + 256 * r;
+      const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
+      *reinterpret_cast<u32x4*>(&tile_lds[buf][item * RS + ch * 16]) = stage[r];
+    }
+    if (PASS == 2 && tid < kTile) lse_lds[buf][tid] = stage_lse;
+  };
+
+  // ---- per-lane running statistics
+  float m_run[2] = {FG_NEG_BIG, FG_NEG_BIG}, l_run[2] = {0.f, 0.f};  // pass 1
+  double col_acc[2] = {0.0, 0.0}, band_acc[2] = {0.0, 0.0};          // pass 2
+  bool snapped[2] = {false, false};
+
+  if (t_begin < t_end) {
+    gload(t_begin);
+    lstore(0);
+  }
+  __syncthreads();
+
+  for (int t = t_begin; t < t_end; ++t) {
+    const int buf = (t - t_begin) & 1;
+    const int t0 = t * kTile;
+    if (t + 1 < t_end) gload(t + 1);
+
+    // what this wave has to do with the tile, per owner fragment
+    bool need[2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      const int Of = O0 + 32 * f;
+      if (PASS == 1) need[f] = (Of < n) && (t0 <= Of + 31);
+      else need[f] = (Of < n) && (t0 + 31 >= Of);
+    }
+
+    if (need[0] || need[1]) {
+      f32x16 acc[2];
+#pragma unroll
+      for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[f][i] = 0.f;
+      const unsigned char* a_ptr = &tile_lds[buf][ln * RS + lh * 16];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_ptr + kk * 32);
+        if (need[0]) acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[0][kk], acc[0], 0, 0, 0);
+        if (need[1]) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[1][kk], acc[1], 0, 0, 0);
+      }
+
+      const int sbase = t0 + lh * 4;  // streamed index of acc[i] = sbase + (i>>2)*8 + (i&3)
+
+      if (PASS == 1) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          if (!need[f]) continue;
+          const int Of = O0 + 32 * f;
+          const int row = Of + ln;
+          if (t0 + 31 <= Of) {  // every column of the tile is visible to every row
+            float tmax = acc[f][0] * c;
+#pragma unroll
+            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[f][i] * c);
+            const float m_new = fmaxf(m_run[f], tmax);
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
+            l_run[f] = l_run[f] * fg_exp2(m_run[f] - m_new) + s;
+            m_run[f] = m_new;
+          } else {  // diagonal tile: causal mask col <= row
+            const int lim = row - sbase;  // valid iff (i>>2)*8 + (i&3) <= lim
+            float tmax = FG_NEG_BIG;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const bool ok = ((i >> 2) * 8 + (i & 3)) <= lim;
+              tmax = fmaxf(tmax, ok ? acc[f][i] * c : FG_NEG_BIG);
+            }
+            const float m_new = fmaxf(m_run[f], tmax);
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const bool ok = ((i >> 2) * 8 + (i & 3)) <= lim;
+              const float p = fg_exp2(fmaf(acc[f][i], c, -m_new));
+              s += ok ? p : 0.f;
+            }
+            l_run[f] = l_run[f] * fg_exp2(m_run[f] - m_new) + s;
+            m_run[f] = m_new;
+          }
+        }
+      } else {
+        // row log-sum-exps of the 16 streamed rows this lane sees
+        float ls[16];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 v = *reinterpret_cast<const f32x4*>(&lse_lds[buf][g * 8 + lh * 4]);
+          ls[g * 4 + 0] = v[0]; ls[g * 4 + 1] = v[1]; ls[g * 4 + 2] = v[2]; ls[g * 4 + 3] = v[3];
+        }
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          if (!need[f]) continue;
+          const int Cf = O0 + 32 * f;
+          const int col = Cf + ln;
+          const bool full = (t0 >= Cf + 31) && (t0 + 31 < n);
+          const bool inside = (t0 + 31 - Cf) < w;   // every element within the local band
+          const bool outside = (t0 - (Cf + 31)) >= w;
+          if (!inside && !snapped[f]) {
+            band_acc[f] = col_acc[f];
+            snapped[f] = true;
+          }
+          if (full && (inside || outside)) {
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -ls[i]));
+            col_acc[f] += (double)s;
+          } else {
+            const int dbase = sbase - col;        // row - col = dbase + (i>>2)*8 + (i&3)
+            const int rlim = n - sbase;           // row < n  iff  (i>>2)*8 + (i&3) < rlim
+            float s = 0.f, sb = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int o = (i >> 2) * 8 + (i & 3);
+              const int dist = dbase + o;
+              const bool ok = (dist >= 0) && (o < rlim);
+              const float p = fg_exp2(fmaf(acc[f][i], c, -ls[i]));
+              s += ok ? p : 0.f;
+              sb += (ok && dist < w) ? p : 0.f;
+            }
+            col_acc[f] += (double)s;
+            if (snapped[f]) band_acc[f] += (double)sb;
+          }
+        }
+      }
+    }
+
+    if (t + 1 < t_end) lstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- merge the two half-waves and store
+  if (PASS == 1) {
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      const float m_o = __shfl_xor(m_run[f], 32, 64);
+      const float l_o = __shfl_xor(l_run[f], 32, 64);
+      const float M = fmaxf(m_run[f], m_o);
+      const float L = l_run[f] * fg_exp2(m_run[f] - M) + l_o * fg_exp2(m_o - M);
+      const int row = O0 + 32 * f + ln;
+      if (lh == 0 && row < n) lse2[(size_t)unit * n + row] = M + __log2f(L);
+    }
+  } else {
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      if (!snapped[f]) band_acc[f] = col_acc[f];
+      const double cs = col_acc[f] + fg_shfl_xor_f64(col_acc[f], 32);
+      const double bs = band_acc[f] + fg_shfl_xor_f64(band_acc[f], 32);
+      const int col = O0 + 32 * f + ln;
+      if (lh == 0 && col < n) {
+        colsum[(size_t)unit * n + col] = cs;
+        bandcol[(size_t)unit * n + col] = bs;
+      }
+    }
+  }
+}
+
+template <int D>
+hipError_t launch(const fg_profile_args& a, hipStream_t s) {
+  const int nblk = (a.n + kOwnPerBlock - 1) / kOwnPerBlock;
+  const int ugroups = (a.U + 7) / 8;
+  const dim3 grid((unsigned)(8 * nblk * ugroups)), block(256);
+  const float c = a.scale * FG_LOG2E;
+  const __bf16* Q = static_cast<const __bf16*>(a.Q);
+  const __bf16* K = static_cast<const __bf16*>(a.K);
+  if (a.run_pass1)
+    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                       a.bandcol, a.U, a.n, a.w, c, nblk);
+  hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                     a.bandcol, a.U, a.n, a.w, c, nblk);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t fg_launch_profile_bf16(const fg_profile_args& a, hipStream_t s) {
+  if (a.d == 128) return launch<128>(a, s);
+  return launch<64>(a, s);
+}

@@ -151,7 +151,7 @@ def unit_plan(w: Workload) -> UnitPlan:
         strength = rng.uniform(1.5, 4.5, size=U)
         strength[pattern == LOCAL] = rng.uniform(6.0, 10.0, size=int((pattern == LOCAL).sum()))
     heavy: List[Optional[np.ndarray]] = [None] * U
-    n_heavy = 8 if w.tiny else max(8, n // 16)
+    n_heavy = min(n - 1, 8 if w.tiny else max(8, n // 16))
     for u in np.nonzero(pattern == HEAVY)[0]:
         r = np.random.default_rng([w.seed, 14, int(u)])
         heavy[u] = np.sort(r.choice(np.arange(1, n), size=n_heavy, replace=False)).astype(np.int64)

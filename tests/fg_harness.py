@@ -1,0 +1,211 @@
+"""Shared machinery of the GPU parity tests: runs the HIP path (through the C ABI) and the
+float64 oracle on the same seeded units and compares them element by element.
+
+Discrete results (policy ids, kept-token sets) must be identical. Two kinds of units are
+set aside by criteria computed by the ORACLE ALONE, counted, and reported:
+  * `margin`   : a recovery R_c lies within 1e-4 of the threshold T, so the policy choice
+                 itself is within float error (the exclusion the benchmark contract allows);
+  * `tie`      : the frequent policy's top-k boundary is closer than `gap_eps` (relative):
+                 which of two nearly equal scores is kept is not decided by float32
+                 arithmetic. From the first such step on, only the set sizes and the
+                 attention output are compared for that unit.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import fastgen_oracle as fo
+from paper_2310_01801_amd import synth
+from paper_2310_01801_amd import binding
+
+MARGIN_EPS = 1e-4
+GAP_EPS = 2e-5          # relative top-k boundary gap below which a unit is "tie-fragile"
+GAP_ABS = 1e-30         # scores this small are below float32's exponent range on the GPU
+
+
+@dataclasses.dataclass
+class Report:
+    units: int = 0
+    margin_excluded: int = 0
+    tie_fragile_profile: int = 0
+    tie_fragile_decode: int = 0
+    max_recovery_err: float = 0.0
+    max_score_rel_err: float = 0.0
+    max_out_err: float = 0.0
+    policies: Dict[int, int] = dataclasses.field(default_factory=dict)
+
+    def line(self) -> str:
+        return (f"units={self.units} policies={dict(sorted(self.policies.items()))} "
+                f"margin_excluded={self.margin_excluded} tie_profile={self.tie_fragile_profile} "
+                f"tie_decode={self.tie_fragile_decode} max|dR|={self.max_recovery_err:.2e} "
+                f"max rel|dscore|={self.max_score_rel_err:.2e} max|do|={self.max_out_err:.2e}")
+
+
+def out_tol(w: synth.Workload) -> float:
+    return 1e-4 if w.dtype == "f32" else 2e-2
+
+
+def scale_of(w: synth.Workload) -> float:
+    return float(np.float32(1.0 / math.sqrt(w.head_dim)))
+
+
+class GpuRun:
+    """The HIP path on a list of units of a workload (each unit carries its own class row)."""
+
+    def __init__(self, w: synth.Workload, units: Sequence[int], device="cuda:0",
+                 forced_policy: int = -1, gen_device: Optional[str] = None, cache_tokens: int = 0):
+        self.w, self.units, self.device = w, list(units), device
+        gen_device = gen_device or device
+        self.plan = synth.unit_plan(w)
+        self.cls_prompt, self.cls_decode = synth.token_classes(w)
+        m = len(self.units)
+        self.Q, self.K, self.V = (t.to(device) for t in
+                                  synth.prompt_batch(w, self.plan, self.cls_prompt, self.units, gen_device))
+        seqs = [u // w.units_per_seq for u in self.units]
+        self.cls_u = torch.from_numpy(self.cls_prompt[seqs].copy()).to(device)          # [m, n]
+        self.cls_dec_u = torch.from_numpy(self.cls_decode[:, seqs].copy()).to(device)   # [S, m]
+        if w.steps > 0:
+            self.q, self.k, self.v = (t.to(device) for t in
+                                      synth.decode_batch(w, self.plan, self.cls_decode, self.units, gen_device))
+        cfg = binding.make_config(m, m, w.head_dim, w.torch_dtype, w.prompt_len, w.steps, w.T, w.r_l,
+                                  w.r_f, 0.0, forced_policy, cache_tokens)
+        self.fg = binding.FastGen(cfg, device)
+        self.forced = forced_policy
+
+    def profile_and_compact(self):
+        pol, rec, cnt = self.fg.fastgen_profile(self.Q, self.K, self.cls_u)
+        self.fg.fastgen_compact(self.K, self.V)
+        torch.cuda.synchronize()
+        return pol.cpu().numpy(), rec.cpu().numpy(), cnt.cpu().numpy()
+
+    def step(self, t: int) -> torch.Tensor:
+        return self.fg.fastgen_decode_step(self.q[t], self.k[t], self.v[t], self.cls_dec_u[t])
+
+    def state(self, rows: bool = False):
+        st = self.fg.fastgen_export_state(rows=rows)
+        assert int(st["status"].item()) == 0, "cache pool overflow reported"
+        off = st["offsets"].cpu().numpy()
+        pos = st["positions"].cpu().numpy()
+        sc = st["scores"].cpu().numpy()
+        out = []
+        for i in range(len(self.units)):
+            out.append((pos[off[i]:off[i + 1]], sc[off[i]:off[i + 1]]))
+        if rows:
+            return out, off, st["keys"], st["values"]
+        return out
+
+
+def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states: bool = True):
+    """Oracle on unit i of a GpuRun: inputs are the exact values the GPU holds, widened."""
+    w = run.w
+    S = w.steps if steps is None else steps
+    f64 = synth.to_f64
+    cls = run.cls_u[i].cpu().numpy()
+    args = (f64(run.Q[i]), f64(run.K[i]), f64(run.V[i]), cls)
+    if S > 0:
+        dec = (f64(run.q[:S, i]), f64(run.k[:S, i]), f64(run.v[:S, i]), run.cls_dec_u[:S, i].cpu().numpy())
+    else:
+        dec = (None, None, None, None)
+    return fo.run_unit(*args, *dec, w.T, w.r_l, w.r_f, scale_of(w), forced_policy=run.forced,
+                       gap_eps=GAP_EPS, record_states=record_states)
+
+
+def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Optional[int] = None,
+            state_steps: Optional[Sequence[int]] = None, check_rows: bool = True) -> Report:
+    """Runs both sides and asserts parity. `check_units` are indices into run.units (default
+    all); `state_steps` are the decode steps after which kept sets and scores are compared
+    (default: every step)."""
+    w = run.w
+    S = w.steps if steps is None else steps
+    idx = list(range(len(run.units))) if check_units is None else list(check_units)
+    rep = Report(units=len(idx))
+    tol = out_tol(w)
+
+    ora = {i: oracle_unit(run, i, S) for i in idx}
+    pol, rec, cnt = run.profile_and_compact()
+
+    excluded = set()     # margin-excluded: nothing discrete is compared
+    fragile_from = {}    # unit -> first decode step (or -1 = from profile) where ties decide
+    for i in idx:
+        p = ora[i]["profile"]
+        rep.policies[p.policy] = rep.policies.get(p.policy, 0) + 1
+        rep.max_recovery_err = max(rep.max_recovery_err, float(np.max(np.abs(rec[i] - p.recovery))))
+        assert np.allclose(rec[i], p.recovery, atol=2e-5), (i, rec[i], p.recovery)
+        if run.forced < 0 and p.margin < MARGIN_EPS:
+            excluded.add(i)
+            rep.margin_excluded += 1
+            continue
+        assert pol[i] == p.policy, f"unit {run.units[i]}: policy {pol[i]} vs oracle {p.policy} R={p.recovery}"
+        tie = p.topk_gap < GAP_EPS or _abs_tie(p.colsum, p.k_f)
+        assert list(cnt[i][:2]) == list(p.cost[:2]) and cnt[i][4] == p.cost[4]
+        if tie:
+            rep.tie_fragile_profile += 1
+            if p.policy in (2, 3):
+                fragile_from[i] = -1
+        else:
+            assert list(cnt[i]) == list(p.cost), (i, cnt[i], p.cost)
+
+    # compaction
+    if check_rows:
+        states, off, keys, values = run.state(rows=True)
+    else:
+        states = run.state()
+    for i in idx:
+        if i in excluded:
+            continue
+        p = ora[i]["profile"]
+        gpos, gsc = states[i]
+        if i in fragile_from:
+            assert gpos.size == ora[i]["init_pos"].size
+            continue
+        assert np.array_equal(gpos, ora[i]["init_pos"]), f"unit {run.units[i]}: kept set after compaction differs"
+        ref = p.colsum[gpos]
+        rel = np.max(np.abs(gsc - ref) / np.maximum(np.abs(ref), 1e-6)) if gpos.size else 0.0
+        rep.max_score_rel_err = max(rep.max_score_rel_err, float(rel))
+        assert rel < 5e-5, (i, rel)
+        if check_rows:
+            kk = keys[off[i]:off[i + 1]]
+            vv = values[off[i]:off[i + 1]]
+            sel = torch.as_tensor(gpos.astype(np.int64), device=kk.device)
+            assert torch.equal(kk, run.K[i][sel]) and torch.equal(vv, run.V[i][sel]), "compacted rows differ"
+
+    # decode
+    state_steps = set(range(S)) if state_steps is None else set(state_steps)
+    for t in range(S):
+        out = run.step(t).float().cpu().numpy()
+        st = run.state() if t in state_steps else None
+        for i in idx:
+            o_ref = ora[i]["outs"][t]
+            if i in excluded:
+                continue
+            fs = ora[i]["cache"].fragile_step
+            if fs >= 0 and t >= fs and i not in fragile_from:
+                fragile_from[i] = fs
+                rep.tie_fragile_decode += 1
+            err = float(np.max(np.abs(out[i] - o_ref)))
+            rep.max_out_err = max(rep.max_out_err, err)
+            assert err <= tol, f"unit {run.units[i]} step {t}: |o - oracle| = {err:.3e} > {tol}"
+            if st is not None:
+                gpos, gsc = st[i]
+                assert gpos.size == ora[i]["lens"][t], f"unit {run.units[i]} step {t}: length {gpos.size} vs {ora[i]['lens'][t]}"
+                if i in fragile_from and t >= fragile_from[i]:
+                    continue
+                assert np.array_equal(gpos, ora[i]["states"][t]), f"unit {run.units[i]} step {t}: kept set differs"
+                if ora[i]["profile"].policy in (2, 3) and gpos.size:
+                    ref = ora[i]["score_states"][t]
+                    rel = float(np.max(np.abs(gsc - ref) / np.maximum(np.abs(ref), 1e-6)))
+                    rep.max_score_rel_err = max(rep.max_score_rel_err, rel)
+                    assert rel < 5e-5, f"unit {run.units[i]} step {t}: score rel err {rel:.2e}"
+    return rep
+
+
+def _abs_tie(colsum: np.ndarray, k: int) -> bool:
+    if k <= 0 or k >= colsum.size:
+        return False
+    s = np.sort(colsum)[::-1]
+    return (s[k - 1] - s[k]) <= GAP_ABS

@@ -1,0 +1,74 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports every symbol the
+header declares, and rejects bad arguments / call orders before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2310_01801_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2310_01801_amd import build
+        build.build(verbose=False)
+    return binding.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "fastgen.h")).read()
+    declared = set(re.findall(r"\b(fastgen_[a-z_]+)\s*\(", header))
+    declared.discard("fastgen_ctx")
+    assert declared == set(binding.EXPORTED)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert b"gfx950" in lib.fastgen_version()
+
+
+def test_config_struct_matches_header():
+    # field order/types of the ctypes mirror against the C declaration
+    header = open(os.path.join(ROOT, "include", "fastgen.h")).read()
+    body = header[header.index("typedef struct {"):header.index("} fg_config;")]
+    names = re.findall(r"^\s*(?:int32_t|int64_t|double|float)\s+([A-Za-z_]+(?:\s*,\s*[A-Za-z_]+)*)\s*;", body, re.M)
+    flat = [x.strip() for grp in names for x in grp.split(",")]
+    assert flat == [f[0] for f in binding.FgConfig._fields_]
+
+
+def _cfg(**kw):
+    base = dict(num_units=8, num_seqs=2, head_dim=128, dtype=binding.torch.bfloat16, prompt_len=64,
+                max_new_tokens=4, T=0.95, r_l=0.3, r_f=0.3)
+    base.update(kw)
+    return binding.make_config(**base)
+
+
+def test_workspace_bytes_and_validation(lib):
+    good = _cfg()
+    nbytes = binding.fastgen_workspace_bytes(good)
+    assert nbytes > 8 * 68 * 128 * 2 * 2 and nbytes % 256 == 0
+    assert binding.fastgen_workspace_bytes(_cfg(cache_tokens=100)) < nbytes
+    for bad in (dict(head_dim=96), dict(num_seqs=3), dict(T=0.0), dict(T=1.5), dict(r_l=-0.1),
+                dict(prompt_len=0), dict(forced_policy=7), dict(num_units=0)):
+        assert binding.fastgen_workspace_bytes(_cfg(**bad)) == 0, bad
+
+
+def test_create_and_call_order_errors_without_launching(lib):
+    cfg = _cfg()
+    nbytes = binding.fastgen_workspace_bytes(cfg)
+    ctx = ctypes.c_void_p()
+    fake = ctypes.c_void_p(0x10000)  # never dereferenced: every call below fails on the host
+    assert lib.fastgen_create(ctypes.byref(cfg), None, nbytes, ctypes.byref(ctx)) == binding.FG_EINVAL
+    assert lib.fastgen_create(ctypes.byref(cfg), ctypes.c_void_p(0x10008), nbytes, ctypes.byref(ctx)) == binding.FG_EINVAL
+    assert lib.fastgen_create(ctypes.byref(cfg), fake, nbytes - 1, ctypes.byref(ctx)) == binding.FG_ENOMEM
+    assert lib.fastgen_create(ctypes.byref(cfg), fake, nbytes, ctypes.byref(ctx)) == binding.FG_OK
+    assert lib.fastgen_profile(ctx, None, None, None, None, None, None, None, None) == binding.FG_EINVAL
+    assert b"required" in lib.fastgen_last_error(ctx)
+    assert lib.fastgen_profile(ctx, 0x10004, 0x10000, 0x10000, None, None, None, None, None) == binding.FG_EINVAL
+    assert lib.fastgen_compact(ctx, 0x10000, 0x10000, None) == binding.FG_ESTATE
+    assert lib.fastgen_decode_step(ctx, 0x10000, 0x10000, 0x10000, 0x10000, 0x10000, None) == binding.FG_ESTATE
+    assert lib.fastgen_export_state(ctx, None, None, None, None, None, None, None, None) == binding.FG_ESTATE
+    assert lib.fastgen_destroy(ctx) == binding.FG_OK
+    assert lib.fastgen_destroy(None) == binding.FG_OK
