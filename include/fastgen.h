@@ -140,6 +140,23 @@ fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offs
                                int32_t* positions, double* scores, void* keys, void* values,
                                int32_t* status, void* stream);
 
+/* Optional device-time accounting per phase (a tracing aid; off by default). When enabled,
+ * every kernel group is bracketed by HIP events on the caller's stream. */
+enum {
+  FG_PHASE_SWEEP1 = 0,      /* QK^T -> row log-sum-exp                       */
+  FG_PHASE_SWEEP2 = 1,      /* QK^T -> softmax -> column / band sums         */
+  FG_PHASE_SELECT = 2,      /* top-k, recoveries, policy, kept flags + scan  */
+  FG_PHASE_COMPACT = 3,     /* pool offsets + gather of kept rows            */
+  FG_PHASE_DECODE_ATTN = 4, /* split-KV attention over the ragged cache      */
+  FG_PHASE_DECODE_UPDATE = 5, /* merge, score update, evict in place         */
+  FG_NUM_PHASES = 6
+};
+fg_status fastgen_enable_timing(fastgen_ctx* ctx, int enable);
+/* Waits for the recorded events, then adds up and clears them.
+ *   ms        host [FG_NUM_PHASES] double: device milliseconds per phase since the last read.
+ *   launches  NULL or host [FG_NUM_PHASES] int64: kernel groups timed per phase. */
+fg_status fastgen_read_timing(fastgen_ctx* ctx, double* ms, int64_t* launches);
+
 /* Message for the last non-OK status returned on this context ("" if none). The string is
  * owned by the context and valid until the next call on it. */
 const char* fastgen_last_error(const fastgen_ctx* ctx);

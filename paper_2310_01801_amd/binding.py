@@ -22,8 +22,9 @@ STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_E
 EXPORTED = (
     "fastgen_workspace_bytes", "fastgen_create", "fastgen_destroy", "fastgen_profile",
     "fastgen_compact", "fastgen_decode_step", "fastgen_export_state", "fastgen_last_error",
-    "fastgen_version",
+    "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing",
 )
+PHASES = ("sweep1", "sweep2", "select", "compact", "decode_attn", "decode_update")
 
 
 class FgConfig(ctypes.Structure):
@@ -69,6 +70,10 @@ def load_library() -> ctypes.CDLL:
     lib.fastgen_export_state.argtypes = [vp] * 9
     lib.fastgen_last_error.restype = ctypes.c_char_p
     lib.fastgen_last_error.argtypes = [vp]
+    lib.fastgen_enable_timing.restype = ctypes.c_int
+    lib.fastgen_enable_timing.argtypes = [vp, ctypes.c_int]
+    lib.fastgen_read_timing.restype = ctypes.c_int
+    lib.fastgen_read_timing.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.fastgen_version.restype = ctypes.c_char_p
     lib.fastgen_version.argtypes = []
     _lib = lib
@@ -101,14 +106,17 @@ def fastgen_workspace_bytes(cfg: FgConfig) -> int:
 class FastGen:
     """One context over a torch-allocated workspace. Methods mirror the C entry points."""
 
-    def __init__(self, cfg: FgConfig, device: str = "cuda:0"):
+    def __init__(self, cfg: FgConfig, device: str = "cuda:0", workspace: Optional[torch.Tensor] = None):
         self.lib = load_library()
         self.cfg = cfg
         self.device = torch.device(device)
         nbytes = fastgen_workspace_bytes(cfg)
         if nbytes == 0:
             raise FastGenError(FG_EINVAL, "invalid configuration")
-        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        if workspace is None:
+            workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        assert workspace.numel() * workspace.element_size() >= nbytes
+        self.workspace = workspace
         self._ctx = ctypes.c_void_p()
         st = self.lib.fastgen_create(ctypes.byref(cfg), self.workspace.data_ptr(), nbytes,
                                      ctypes.byref(self._ctx))
@@ -130,6 +138,15 @@ class FastGen:
     def _check(self, st: int) -> None:
         if st != FG_OK:
             raise FastGenError(st, self.lib.fastgen_last_error(self._ctx).decode())
+
+    def fastgen_enable_timing(self, enable: bool = True) -> None:
+        self._check(self.lib.fastgen_enable_timing(self._ctx, 1 if enable else 0))
+
+    def fastgen_read_timing(self) -> Dict[str, Tuple[float, int]]:
+        ms = (ctypes.c_double * len(PHASES))()
+        cnt = (ctypes.c_int64 * len(PHASES))()
+        self._check(self.lib.fastgen_read_timing(self._ctx, ms, cnt))
+        return {name: (float(ms[i]), int(cnt[i])) for i, name in enumerate(PHASES)}
 
     # -- stage 1
     def fastgen_profile(self, Q: torch.Tensor, K: torch.Tensor, token_class: torch.Tensor,
@@ -155,7 +172,7 @@ class FastGen:
                                                  _ptr(class_new), _ptr(out), _stream()))
         return out
 
-    def fastgen_export_state(self, rows: bool = False) -> Dict[str, torch.Tensor]:
+    def fastgen_export_state(self, rows: bool = False, lengths_only: bool = False) -> Dict[str, torch.Tensor]:
         U, d = self.cfg.num_units, self.cfg.head_dim
         lengths = torch.empty(U, dtype=torch.int32, device=self.device)
         offsets = torch.empty(U + 1, dtype=torch.int64, device=self.device)
@@ -163,6 +180,8 @@ class FastGen:
         # first the lengths, to size the packed outputs
         self._check(self.lib.fastgen_export_state(self._ctx, _ptr(lengths), _ptr(offsets), None, None,
                                                   None, None, _ptr(status), _stream()))
+        if lengths_only:
+            return dict(lengths=lengths, offsets=offsets, status=status)
         total = int(offsets[-1].item())
         positions = torch.empty(max(total, 1), dtype=torch.int32, device=self.device)
         scores = torch.empty(max(total, 1), dtype=torch.float64, device=self.device)

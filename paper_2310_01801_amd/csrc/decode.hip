@@ -279,16 +279,28 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   if (tid == 0) a.len[u] = new_len;
 }
 
-template <int ESIZE, int D>
-hipError_t launch(const fg_decode_args& a, hipStream_t s) {
-  hipLaunchKernelGGL((fg_decode_partial_kernel<ESIZE, D>), dim3((unsigned)a.max_chunks), dim3(256), 0, s, a);
-  hipLaunchKernelGGL((fg_decode_finish_kernel<ESIZE, D>), dim3((unsigned)a.U), dim3(256), 0, s, a);
+}  // namespace
+
+hipError_t fg_launch_decode_attn(const fg_decode_args& a, hipStream_t s) {
+  const dim3 grid((unsigned)a.max_chunks), block(256);
+  if (a.dtype == FG_BF16) {
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<2, 128>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<2, 64>), grid, block, 0, s, a);
+  } else {
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<4, 128>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<4, 64>), grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 
-}  // namespace
-
-hipError_t fg_launch_decode(const fg_decode_args& a, hipStream_t s) {
-  if (a.dtype == FG_BF16) return a.d == 128 ? launch<2, 128>(a, s) : launch<2, 64>(a, s);
-  return a.d == 128 ? launch<4, 128>(a, s) : launch<4, 64>(a, s);
+hipError_t fg_launch_decode_update(const fg_decode_args& a, hipStream_t s) {
+  const dim3 grid((unsigned)a.U), block(256);
+  if (a.dtype == FG_BF16) {
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<2, 128>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_finish_kernel<2, 64>), grid, block, 0, s, a);
+  } else {
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<4, 128>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_finish_kernel<4, 64>), grid, block, 0, s, a);
+  }
+  return hipGetLastError();
 }

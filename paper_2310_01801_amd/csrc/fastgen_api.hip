@@ -94,6 +94,26 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <class T>
 T* at(fastgen_ctx* ctx, size_t off) { return reinterpret_cast<T*>(ctx->ws + off); }
 
+// Brackets one kernel group with events when device-time accounting is on.
+struct PhaseTimer {
+  fastgen_ctx* ctx; hipStream_t s; fastgen_ctx::timed rec; bool on;
+  PhaseTimer(fastgen_ctx* c, int phase, hipStream_t st) : ctx(c), s(st), on(c->timing) {
+    if (!on) return;
+    rec.phase = phase;
+    hipEvent_t* ev[2] = {&rec.a, &rec.b};
+    for (auto e : ev) {
+      if (!ctx->spare.empty()) { *e = ctx->spare.back(); ctx->spare.pop_back(); }
+      else if (hipEventCreate(e) != hipSuccess) { on = false; return; }
+    }
+    (void)hipEventRecord(rec.a, s);
+  }
+  ~PhaseTimer() {
+    if (!on) return;
+    (void)hipEventRecord(rec.b, s);
+    ctx->pending.push_back(rec);
+  }
+};
+
 }  // namespace
 
 extern "C" {
@@ -111,9 +131,9 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0) return FG_EINVAL;
   fg_layout lay = make_layout(*cfg);
   if (bytes < lay.total) return FG_ENOMEM;
-  fastgen_ctx* ctx = new (std::nothrow) fastgen_ctx;
+  fastgen_ctx* ctx = new (std::nothrow) fastgen_ctx();
   if (!ctx) return FG_ENOMEM;
-  memset(ctx, 0, sizeof(*ctx));
+  ctx->timing = false;
   ctx->cfg = *cfg;
   ctx->lay = lay;
   ctx->ws = static_cast<char*>(workspace);
@@ -128,8 +148,35 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
 }
 
 fg_status fastgen_destroy(fastgen_ctx* ctx) {
+  if (!ctx) return FG_OK;
+  for (auto& r : ctx->pending) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : ctx->spare) (void)hipEventDestroy(e);
   delete ctx;
   return FG_OK;
+}
+
+fg_status fastgen_enable_timing(fastgen_ctx* ctx, int enable) {
+  if (!ctx) return FG_EINVAL;
+  ctx->timing = enable != 0;
+  return FG_OK;
+}
+
+fg_status fastgen_read_timing(fastgen_ctx* ctx, double* ms, int64_t* launches) {
+  if (!ctx) return FG_EINVAL;
+  if (!ms) return fail(ctx, FG_EINVAL, "fastgen_read_timing: ms is required");
+  for (int i = 0; i < FG_NUM_PHASES; ++i) { ms[i] = 0.0; if (launches) launches[i] = 0; }
+  fg_status st = FG_OK;
+  for (auto& r : ctx->pending) {
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    if (e != hipSuccess) st = hip_fail(ctx, e, "fastgen_read_timing");
+    else { ms[r.phase] += (double)t; if (launches) launches[r.phase] += 1; }
+    ctx->spare.push_back(r.a);
+    ctx->spare.push_back(r.b);
+  }
+  ctx->pending.clear();
+  return st;
 }
 
 fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const uint8_t* token_class,
@@ -150,14 +197,18 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   pa.bandcol = at<double>(ctx, L.bandcol);
   pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w;
   pa.scale = ctx->scale;
-  pa.run_pass1 = (lse_opt == nullptr);
   hipError_t e;
-  if (lse_opt) {
-    e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * c.prompt_len, s);
-    if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(lse)");
+  {
+    PhaseTimer tm(ctx, FG_PHASE_SWEEP1, s);
+    if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * c.prompt_len, s);
+    else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
   }
-  e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, s) : fg_launch_profile_f32(pa, s);
-  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(attention sweeps)");
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(row log-sum-exp sweep)");
+  {
+    PhaseTimer tm(ctx, FG_PHASE_SWEEP2, s);
+    e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 2, s) : fg_launch_profile_f32(pa, 2, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(column sweep)");
 
   fg_select_args sa;
   sa.colsum = pa.colsum; sa.bandcol = pa.bandcol; sa.token_class = token_class;
@@ -169,7 +220,10 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
   sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f;
   sa.forced_policy = c.forced_policy;
-  e = fg_launch_select(sa, s);
+  {
+    PhaseTimer tm(ctx, FG_PHASE_SELECT, s);
+    e = fg_launch_select(sa, s);
+  }
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(select)");
   ctx->stage = 1;
   return FG_OK;
@@ -183,6 +237,7 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const fg_config& c = ctx->cfg;
   const fg_layout& L = ctx->lay;
+  PhaseTimer tm(ctx, FG_PHASE_COMPACT, s);
   hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int64_t>(ctx, L.off),
                                    at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
                                    at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
@@ -234,8 +289,18 @@ fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new
   da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;
   da.units_per_seq = c.num_units / c.num_seqs; da.w = ctx->w; da.step = ctx->steps_done;
   da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks;
-  hipError_t e = fg_launch_decode(da, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  {
+    PhaseTimer tm(ctx, FG_PHASE_DECODE_ATTN, s);
+    e = fg_launch_decode_attn(da, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step(attention)");
+  {
+    PhaseTimer tm(ctx, FG_PHASE_DECODE_UPDATE, s);
+    e = fg_launch_decode_update(da, s);
+  }
+  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step(update)");
   ctx->steps_done += 1;
   return FG_OK;
 }

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/fastgen.h"
 
 // ---------------------------------------------------------------- workspace layout
@@ -49,6 +51,11 @@ struct fastgen_ctx {
   int stage;        // 0 created, 1 profiled, 2 compacted / decoding
   int steps_done;
   char err[256];
+  // optional device-time accounting
+  bool timing;
+  struct timed { int phase; hipEvent_t a, b; };
+  std::vector<timed> pending;
+  std::vector<hipEvent_t> spare;
 };
 
 constexpr int FG_DECODE_CHUNK = 256;  // tokens per split-KV work item
@@ -59,7 +66,6 @@ struct fg_profile_args {
   float* lse2; double* colsum; double* bandcol;
   int U, n, d, w;
   float scale;
-  bool run_pass1;
 };
 
 struct fg_select_args {
@@ -100,13 +106,14 @@ struct fg_export_args {
   int U, d, esize, max_pos;  // max_pos = n + S
 };
 
-hipError_t fg_launch_profile_bf16(const fg_profile_args&, hipStream_t);
-hipError_t fg_launch_profile_f32(const fg_profile_args&, hipStream_t);
+hipError_t fg_launch_profile_bf16(const fg_profile_args&, int pass, hipStream_t);
+hipError_t fg_launch_profile_f32(const fg_profile_args&, int pass, hipStream_t);
 hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t);
 hipError_t fg_launch_select(const fg_select_args&, hipStream_t);
 hipError_t fg_launch_compact(const fg_compact_args&, hipStream_t);
 hipError_t fg_launch_offsets(const int32_t* cap, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
                              int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
                              hipStream_t);
-hipError_t fg_launch_decode(const fg_decode_args&, hipStream_t);
+hipError_t fg_launch_decode_attn(const fg_decode_args&, hipStream_t);
+hipError_t fg_launch_decode_update(const fg_decode_args&, hipStream_t);
 hipError_t fg_launch_export(const fg_export_args&, hipStream_t);

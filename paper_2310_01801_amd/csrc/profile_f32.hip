@@ -81,17 +81,18 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
 }
 
 template <int D>
-hipError_t launch(const fg_profile_args& a, hipStream_t s) {
+hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const int nblk = (a.n + 255) / 256;
   const dim3 grid((unsigned)((size_t)nblk * a.U)), block(256);
   const float c = a.scale * FG_LOG2E;
   const float* Q = static_cast<const float*>(a.Q);
   const float* K = static_cast<const float*>(a.K);
-  if (a.run_pass1)
+  if (pass == 1)
     hipLaunchKernelGGL((fg_profile_f32_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
                        a.bandcol, a.n, a.w, c, nblk);
-  hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                     a.bandcol, a.n, a.w, c, nblk);
+  else
+    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                       a.bandcol, a.n, a.w, c, nblk);
   return hipGetLastError();
 }
 
@@ -102,9 +103,9 @@ __global__ void fg_lse_to_log2_kernel(const float* __restrict__ in, float* __res
 
 }  // namespace
 
-hipError_t fg_launch_profile_f32(const fg_profile_args& a, hipStream_t s) {
-  if (a.d == 128) return launch<128>(a, s);
-  return launch<64>(a, s);
+hipError_t fg_launch_profile_f32(const fg_profile_args& a, int pass, hipStream_t s) {
+  if (a.d == 128) return launch<128>(a, pass, s);
+  return launch<64>(a, pass, s);
 }
 
 hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t s) {

@@ -262,24 +262,25 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 }
 
 template <int D>
-hipError_t launch(const fg_profile_args& a, hipStream_t s) {
+hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const int nblk = (a.n + kOwnPerBlock - 1) / kOwnPerBlock;
   const int ugroups = (a.U + 7) / 8;
   const dim3 grid((unsigned)(8 * nblk * ugroups)), block(256);
   const float c = a.scale * FG_LOG2E;
   const __bf16* Q = static_cast<const __bf16*>(a.Q);
   const __bf16* K = static_cast<const __bf16*>(a.K);
-  if (a.run_pass1)
+  if (pass == 1)
     hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
                        a.bandcol, a.U, a.n, a.w, c, nblk);
-  hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                     a.bandcol, a.U, a.n, a.w, c, nblk);
+  else
+    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+                       a.bandcol, a.U, a.n, a.w, c, nblk);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t fg_launch_profile_bf16(const fg_profile_args& a, hipStream_t s) {
-  if (a.d == 128) return launch<128>(a, s);
-  return launch<64>(a, s);
+hipError_t fg_launch_profile_bf16(const fg_profile_args& a, int pass, hipStream_t s) {
+  if (a.d == 128) return launch<128>(a, pass, s);
+  return launch<64>(a, pass, s);
 }
