@@ -52,7 +52,8 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   if (unit >= U) return;
   const int blk = (PASS == 1) ? (nblk - 1 - blk_ord) : blk_ord;  // heaviest first
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int ln = lane & 31, lh = lane >> 5;
   const size_t base = (size_t)unit * (size_t)n * D;
   const __bf16* own_mat = (PASS == 1 ? Q : K) + base;
@@ -66,11 +67,11 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   bf16x8 own[2][KK];
 #pragma unroll
   for (int f = 0; f < 2; ++f) {
-    const int item = O0 + 32 * f + ln;
+    // items past the end are clamped to the last one: their results are never stored
+    const int item = min(O0 + 32 * f + ln, n - 1);
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (item < n) v = *reinterpret_cast<const u32x4*>(own_mat + (size_t)item * D + lh * 8 + 16 * kk);
+      const u32x4 v = *reinterpret_cast<const u32x4*>(own_mat + (size_t)item * D + lh * 8 + 16 * kk);
       own[f][kk] = __builtin_bit_cast(bf16x8, v);
     }
   }
@@ -93,11 +94,11 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
     for (int r = 0; r < LOADS; ++r) {
       const int q = tid + 256 * r;
       const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (t0 + item < n) v = *reinterpret_cast<const u32x4*>(str_mat + (size_t)(t0 + item) * D + ch * 8);
-      stage[r] = v;
+      // rows past the end repeat the last row; every use of them is masked (causal / tail)
+      const int row = min(t0 + item, n - 1);
+      stage[r] = *reinterpret_cast<const u32x4*>(str_mat + (size_t)row * D + ch * 8);
     }
-    if (PASS == 2 && tid < kTile) stage_lse = (t0 + tid < n) ? lse_row[t0 + tid] : 0.f;
+    if (PASS == 2) stage_lse = lse_row[min(t0 + (tid & (kTile - 1)), n - 1)];
   };
   auto lstore = [&](int buf) {
 #pragma unroll
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   for (int t = t_begin; t < t_end; ++t) {
     const int buf = (t - t_begin) & 1;
     const int t0 = t * kTile;
-    if (t + 1 < t_end) gload(t + 1);
+    gload(min(t + 1, t_end - 1));  // unconditional: the load count per iteration is static
 
     // what this wave has to do with the tile, per owner fragment
     bool need[2];
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
       else need[f] = (Of < n) && (t0 + 31 >= Of);
     }
 
-    if (need[0] || need[1]) {
+    if (need[0] || need[1]) {  // scalar branch: `wave` is uniform
       f32x16 acc[2];
 #pragma unroll
       for (int f = 0; f < 2; ++f)
@@ -144,8 +145,8 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_ptr + kk * 32);
-        if (need[0]) acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[0][kk], acc[0], 0, 0, 0);
-        if (need[1]) acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[1][kk], acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[0][kk], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, own[1][kk], acc[1], 0, 0, 0);
       }
 
       const int sbase = t0 + lh * 4;  // streamed index of acc[i] = sbase + (i>>2)*8 + (i&3)
@@ -157,10 +158,10 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
           const int Of = O0 + 32 * f;
           const int row = Of + ln;
           if (t0 + 31 <= Of) {  // every column of the tile is visible to every row
-            float tmax = acc[f][0] * c;
+            float tmax = acc[f][0];
 #pragma unroll
-            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[f][i] * c);
-            const float m_new = fmaxf(m_run[f], tmax);
+            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[f][i]);
+            const float m_new = fmaxf(m_run[f], tmax * c);  // c > 0
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
       }
     }
 
-    if (t + 1 < t_end) lstore(buf ^ 1);
+    lstore(buf ^ 1);
     __syncthreads();
   }
 
