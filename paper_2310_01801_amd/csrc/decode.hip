@@ -46,20 +46,23 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   __shared__ float s_red[8];
   __shared__ float s_o[4][D];
 
-  if (a.flags[0] != 0) return;
+  // header: everything static comes from one 32-byte record; only the length is looked up
   const int item = blockIdx.x;
-  if (item >= a.chunk_off[a.U]) return;
-  const int u = a.item_unit[item];
-  const int chunk = item - a.chunk_off[u];
+  const int n_items = a.chunk_off[a.U];
+  const int overflow = a.flags[0];
+  const int4 rec = *reinterpret_cast<const int4*>(a.item_unit + (size_t)item * 8);
+  const int2 rec_off = *reinterpret_cast<const int2*>(a.item_unit + (size_t)item * 8 + 4);
+  if (overflow != 0 || item >= n_items) return;
+  const int u = rec.x, chunk = rec.y;
   const int Lold = a.len[u], L = Lold + 1;
   const int start = chunk * CH;
   if (start >= L) return;
-  if (L > a.cap[u]) {  // cannot happen while the host bounds the step count
+  if (L > rec.z) {  // cannot happen while the host bounds the step count
     if (threadIdx.x == 0) a.flags[0] = 1;
     return;
   }
   const int cnt = min(CH, L - start);
-  const int64_t off = a.off[u];
+  const int64_t off = ((int64_t)rec_off.y << 32) | (uint32_t)rec_off.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane % LPR, sub = lane / LPR;
   const float c = a.scale * FG_LOG2E;
@@ -207,11 +210,42 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   double* score = a.cscore + off;
   const int32_t* pos = a.cpos + off;
   const uint8_t* cls = a.ccls + off;
+  const int cmask = FG_CLASS_SPECIAL | (policy >= 1 ? FG_CLASS_PUNCT : 0);
+  const int wlo = (policy >= 3) ? p_new - a.w : 0x7fffffff;  // positions above wlo are inside the window
 
+  // Fast path (L <= 256 * NC): each thread keeps its slots' updated scores and a "protected"
+  // bit (special / punctuation / window) in registers, so every later phase is register-only.
+  constexpr int NC = 24;
+  uint64_t kc[NC];
+  uint32_t prot = 0;
+  const bool small = L <= 256 * NC;
   fg_topk tk;
   tk.mode = 0; tk.thr = 0; tk.pthr = 0;
-  if (policy >= 2) {
-    // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
+  if (small) {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      kc[i] = 0;
+      if (j < L) {
+        const int cb = cls[j];
+        const int pj = pos[j];
+        if ((cb & cmask) != 0 || pj > wlo) prot |= 1u << i;
+        if (policy >= 2) {
+          // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
+          const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
+          const double sc = score[j] + (double)aj;
+          score[j] = sc;
+          kc[i] = (uint64_t)__double_as_longlong(sc);
+        }
+      }
+    }
+    if (policy >= 2) {
+      const int k_f = fg_budget(a.r_f, p_new + 1);
+      __syncthreads();  // score[] is re-read by other threads only if the boundary value is tied
+      tk = fg_select_topk_regs<NC>(kc, [&](int j) { return score[j]; },
+                                   [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
+    }
+  } else if (policy >= 2) {
     for (int j = tid; j < L; j += 256) {
       const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
       score[j] += (double)aj;
@@ -220,16 +254,31 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     const int k_f = fg_budget(a.r_f, p_new + 1);
     tk = fg_select_topk([&](int j) { return score[j]; }, [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
   }
-  auto kept = [&](int j) -> bool {
-    const int cbits = cls[j];
-    bool k = (cbits & FG_CLASS_SPECIAL) != 0;
-    if (policy >= 1) k = k || (cbits & FG_CLASS_PUNCT) != 0;
+  const bool tie_pos = (tk.mode == 2 && tk.pthr != 0xffffffffu);  // rare: boundary value shared
+  auto kept = [&](int j) -> bool {  // from memory (large units and the tied case)
+    bool k = (cls[j] & cmask) != 0 || pos[j] > wlo;
     if (policy >= 2) k = k || fg_in_topk(tk, score[j], (uint32_t)pos[j]);
-    if (policy >= 3) k = k || (pos[j] > p_new - a.w);
     return k;
   };
+  uint32_t keepbits = 0;  // fast path: bit i = slot tid + 256 i stays
   int mine = 0;
-  for (int j = tid; j < L; j += 256) mine += kept(j) ? 1 : 0;
+  if (small) {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      if (j < L) {
+        bool k = (prot >> i) & 1u;
+        if (policy >= 2 && !k) {
+          if (tk.mode == 1) k = true;
+          else if (tk.mode == 2) k = tie_pos ? fg_in_topk(tk, __longlong_as_double((long long)kc[i]), (uint32_t)pos[j])
+                                             : (kc[i] >= tk.thr);
+        }
+        if (k) { keepbits |= 1u << i; ++mine; }
+      }
+    }
+  } else {
+    for (int j = tid; j < L; j += 256) mine += kept(j) ? 1 : 0;
+  }
   const int new_len = fg_block_sum_i32(mine, ired);
   if (new_len == L) {
     if (tid == 0) a.len[u] = L;
@@ -241,23 +290,53 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const int cap = a.cap[u];
   __syncthreads();
   int run_h = 0, run_m = 0;
-  for (int base = 0; base < L; base += 256) {
-    const int j = base + tid;
-    int is_h = 0, is_m = 0;
-    if (j < L) {
-      const bool k = kept(j);
-      is_h = (j < new_len && !k) ? 1 : 0;
-      is_m = (j >= new_len && k) ? 1 : 0;
+  if (small) {
+    // any one-to-one pairing of holes and movers will do: number them thread by thread
+    int nh = 0, nm = 0;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      if (j < L) {
+        const bool k = (keepbits >> i) & 1u;
+        nh += (j < new_len && !k) ? 1 : 0;
+        nm += (j >= new_len && k) ? 1 : 0;
+      }
     }
     int tot_h, tot_m;
-    const int ex_h = fg_block_exscan_i32(is_h, ired, &tot_h);
+    int at_h = fg_block_exscan_i32(nh, ired, &tot_h);
     __syncthreads();
-    const int ex_m = fg_block_exscan_i32(is_m, ired, &tot_m);
-    if (is_h) scratch[run_h + ex_h] = j;
-    if (is_m) scratch[cap - 1 - (run_m + ex_m)] = j;
-    run_h += tot_h;
-    run_m += tot_m;
+    int at_m = fg_block_exscan_i32(nm, ired, &tot_m);
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      if (j < L) {
+        const bool k = (keepbits >> i) & 1u;
+        if (j < new_len && !k) scratch[at_h++] = j;
+        if (j >= new_len && k) scratch[cap - 1 - (at_m++)] = j;
+      }
+    }
+    run_h = tot_h;
+    run_m = tot_m;
     __syncthreads();
+  } else {
+    for (int base = 0; base < L; base += 256) {
+      const int j = base + tid;
+      int is_h = 0, is_m = 0;
+      if (j < L) {
+        const bool k = kept(j);
+        is_h = (j < new_len && !k) ? 1 : 0;
+        is_m = (j >= new_len && k) ? 1 : 0;
+      }
+      int tot_h, tot_m;
+      const int ex_h = fg_block_exscan_i32(is_h, ired, &tot_h);
+      __syncthreads();
+      const int ex_m = fg_block_exscan_i32(is_m, ired, &tot_m);
+      if (is_h) scratch[run_h + ex_h] = j;
+      if (is_m) scratch[cap - 1 - (run_m + ex_m)] = j;
+      run_h += tot_h;
+      run_m += tot_m;
+      __syncthreads();
+    }
   }
   const int moves = run_h;  // == run_m
   char* ck = static_cast<char*>(a.ck) + off * RB;

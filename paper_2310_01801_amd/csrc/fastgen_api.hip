@@ -69,7 +69,7 @@ fg_layout make_layout(const fg_config& c) {
   L.ccls = take(pool);
   L.clogit = take(pool * 4);
   L.chunk_off = take((U + 1) * 4);
-  L.item_unit = take((size_t)L.max_chunks * 4);
+  L.item_unit = take((size_t)L.max_chunks * 32);
   L.part = take((size_t)L.max_chunks * (d + 2) * 4);
   L.total = o;
   return L;

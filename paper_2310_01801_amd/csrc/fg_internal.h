@@ -35,7 +35,7 @@ struct fg_layout {
   size_t clogit;    // [pool] float   this step's scaled logit of every held token
   // decode scratch
   size_t chunk_off; // [U + 1] int32  first chunk of each unit in the flat work list
-  size_t item_unit; // [max_chunks] int32  unit of every work item (-1: unused)
+  size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, 1, pool offset lo/hi, 0, 0
   size_t part;      // [max_chunks, d + 2] float  split-KV partial (max, sum, o)
   size_t total;
   int64_t pool_tokens;

@@ -1,20 +1,27 @@
 // Block-wide exact selection of the k largest of m non-negative doubles with the tie rule
 // "equal score -> the smaller position is kept" (the frequent policy of Sec. 3.4 keeps the
 // tokens with the largest cumulative attention score). MSB-first radix select on the IEEE
-// bit patterns (monotone for non-negative doubles), 8 bits per pass, then -- only if the
-// boundary value is shared -- the same select on the positions of the tied elements.
+// bit patterns (monotone for non-negative doubles), 8 bits per pass:
+//   * keys are held in registers when m <= 256 * FG_SEL_CACHE (else re-read each pass);
+//   * passes over the bits that all keys share are skipped (block-wide OR/AND of the keys);
+//   * the scan stops as soon as the boundary bucket is taken whole;
+//   * only if the boundary value is shared does a second select run on the positions.
+// blockDim.x must be 256.
 #pragma once
 #include "fg_common.h"
 
+#define FG_SEL_CACHE 12
+
 struct fg_topk {
-  uint64_t thr;   // bit pattern of the k-th largest score
-  uint32_t pthr;  // among scores == thr, positions <= pthr are inside the top-k
+  uint64_t thr;   // keys above thr are in; keys equal to thr are in iff pos <= pthr
+  uint32_t pthr;
   int mode;       // 0: nothing selected, 1: everything selected, 2: use (thr, pthr)
 };
 
 struct fg_select_smem {
   int hist[256];
   int red[20];
+  unsigned long long w_or[4], w_and[4];
   int digit, rem, cnt;
 };
 
@@ -24,21 +31,10 @@ __device__ __forceinline__ bool fg_in_topk(const fg_topk& t, double score, uint3
   return key > t.thr || (key == t.thr && pos <= t.pthr);
 }
 
-// One radix pass: histogram of the digit at `shift` over active elements whose key matches
-// `prefix` under `mask`, then locate the digit that holds the rem-th largest.
-// KeyFn(j, &key) returns false for inactive elements. blockDim.x must be 256.
-template <class KeyFn>
-__device__ __forceinline__ void fg_radix_pass(KeyFn keyfn, int m, int shift, uint64_t prefix,
-                                              uint64_t mask, int rem, fg_select_smem* sm) {
+// After the histogram of one digit is complete: locate the bucket that holds the rem-th
+// largest. Thread t looks at bucket 255 - t (descending order).
+__device__ __forceinline__ void fg_radix_locate(int rem, fg_select_smem* sm) {
   const int tid = threadIdx.x;
-  sm->hist[tid] = 0;
-  __syncthreads();
-  for (int j = tid; j < m; j += 256) {
-    uint64_t key;
-    if (keyfn(j, &key) && (key & mask) == prefix) atomicAdd(&sm->hist[(int)((key >> shift) & 255u)], 1);
-  }
-  __syncthreads();
-  // thread t looks at bucket 255 - t: buckets in descending order
   const int h = sm->hist[255 - tid];
   int total;
   const int before = fg_block_exscan_i32(h, sm->red, &total);
@@ -50,6 +46,117 @@ __device__ __forceinline__ void fg_radix_pass(KeyFn keyfn, int m, int shift, uin
   __syncthreads();
 }
 
+// NC > 0: element tid + 256 i of the block is kc[i] (registers); NC == 0: keys come from score(j).
+template <int NC, class ScoreFn, class PosFn>
+__device__ __forceinline__ fg_topk fg_select_topk_impl(const uint64_t (&kc)[NC > 0 ? NC : 1], ScoreFn score,
+                                                       PosFn pos, int m, int k, fg_select_smem* sm) {
+  constexpr bool CACHED = NC > 0;
+  fg_topk r;
+  r.thr = 0; r.pthr = 0xffffffffu; r.mode = 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  // ---- the bits the keys do not all share
+  uint64_t k_or = 0, k_and = ~0ull;
+  if (CACHED) {
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      if (j < m) {
+        k_or |= kc[i];
+        k_and &= kc[i];
+      }
+    }
+  } else {
+    for (int j = tid; j < m; j += 256) {
+      const uint64_t key = (uint64_t)__double_as_longlong(score(j));
+      k_or |= key;
+      k_and &= key;
+    }
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    k_or |= ((uint64_t)__shfl_xor((int)(k_or >> 32), o, 64) << 32) | (uint32_t)__shfl_xor((int)k_or, o, 64);
+    k_and &= ((uint64_t)__shfl_xor((int)(k_and >> 32), o, 64) << 32) | (uint32_t)__shfl_xor((int)k_and, o, 64);
+  }
+  __syncthreads();
+  if (lane == 0) { sm->w_or[wave] = k_or; sm->w_and[wave] = k_and; }
+  __syncthreads();
+  k_or = sm->w_or[0] | sm->w_or[1] | sm->w_or[2] | sm->w_or[3];
+  k_and = sm->w_and[0] & sm->w_and[1] & sm->w_and[2] & sm->w_and[3];
+  const uint64_t diff = k_or ^ k_and;
+
+  uint64_t prefix = 0, mask = 0;
+  int rem = k, n_eq = m;
+  if (diff != 0) {
+    const int top = 63 - __clzll((long long)diff);  // highest bit in which two keys differ
+    int shift = (top >> 3) << 3;
+    mask = (shift + 8 >= 64) ? 0ull : ~((1ull << (shift + 8)) - 1ull);
+    prefix = k_and & mask;
+    for (; shift >= 0; shift -= 8) {
+      sm->hist[tid] = 0;
+      __syncthreads();
+      if (CACHED) {
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+          const int j = tid + 256 * i;
+          if (j < m && (kc[i] & mask) == prefix) atomicAdd(&sm->hist[(int)((kc[i] >> shift) & 255u)], 1);
+        }
+      } else {
+        for (int j = tid; j < m; j += 256) {
+          const uint64_t key = (uint64_t)__double_as_longlong(score(j));
+          if ((key & mask) == prefix) atomicAdd(&sm->hist[(int)((key >> shift) & 255u)], 1);
+        }
+      }
+      __syncthreads();
+      fg_radix_locate(rem, sm);
+      prefix |= (uint64_t)sm->digit << shift;
+      mask |= (uint64_t)0xff << shift;
+      rem = sm->rem;
+      n_eq = sm->cnt;
+      if (rem == n_eq) {  // the boundary bucket is taken whole: every key >= prefix is in
+        r.thr = prefix;
+        return r;
+      }
+    }
+  } else {
+    prefix = k_and;  // all keys are equal
+  }
+  r.thr = prefix;
+  if (rem == n_eq) return r;
+  // ties at the boundary value: keep the `rem` smallest positions among the tied elements,
+  // i.e. select the rem-th largest of (~pos) over them
+  const uint64_t thr = prefix;
+  uint64_t p2 = 0, m2 = 0;
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    sm->hist[tid] = 0;
+    __syncthreads();
+    for (int j = tid; j < m; j += 256) {
+      if ((uint64_t)__double_as_longlong(score(j)) != thr) continue;
+      const uint64_t key = (uint64_t)(0xffffffffu - pos(j));
+      if ((key & m2) == p2) atomicAdd(&sm->hist[(int)((key >> shift) & 255u)], 1);
+    }
+    __syncthreads();
+    fg_radix_locate(rem, sm);
+    p2 |= (uint64_t)sm->digit << shift;
+    m2 |= (uint64_t)0xff << shift;
+    rem = sm->rem;
+  }
+  r.pthr = 0xffffffffu - (uint32_t)p2;
+  return r;
+}
+
+// Keys already in registers (element tid + 256 i is kc[i], i < NC, valid while < m).
+// score(j) / pos(j) are only consulted if the boundary value is tied.
+template <int NC, class ScoreFn, class PosFn>
+__device__ __forceinline__ fg_topk fg_select_topk_regs(const uint64_t (&kc)[NC], ScoreFn score, PosFn pos,
+                                                       int m, int k, fg_select_smem* sm) {
+  fg_topk r;
+  r.thr = 0; r.pthr = 0;
+  if (k <= 0) { r.mode = 0; return r; }
+  if (k >= m) { r.mode = 1; return r; }
+  return fg_select_topk_impl<NC>(kc, score, pos, m, k, sm);
+}
+
 // ScoreFn(j) -> double (>= 0), PosFn(j) -> uint32 position (unique per element).
 template <class ScoreFn, class PosFn>
 __device__ __forceinline__ fg_topk fg_select_topk(ScoreFn score, PosFn pos, int m, int k,
@@ -58,34 +165,15 @@ __device__ __forceinline__ fg_topk fg_select_topk(ScoreFn score, PosFn pos, int 
   r.thr = 0; r.pthr = 0;
   if (k <= 0) { r.mode = 0; return r; }
   if (k >= m) { r.mode = 1; return r; }
-  r.mode = 2;
-  uint64_t prefix = 0, mask = 0;
-  int rem = k;
-  auto key1 = [&](int j, uint64_t* key) { *key = (uint64_t)__double_as_longlong(score(j)); return true; };
-  for (int shift = 56; shift >= 0; shift -= 8) {
-    fg_radix_pass(key1, m, shift, prefix, mask, rem, sm);
-    prefix |= (uint64_t)sm->digit << shift;
-    mask |= (uint64_t)0xff << shift;
-    rem = sm->rem;
+  if (m <= 256 * FG_SEL_CACHE) {
+    uint64_t kc[FG_SEL_CACHE];
+#pragma unroll
+    for (int i = 0; i < FG_SEL_CACHE; ++i) {
+      const int j = threadIdx.x + 256 * i;
+      kc[i] = (j < m) ? (uint64_t)__double_as_longlong(score(j)) : 0ull;
+    }
+    return fg_select_topk_impl<FG_SEL_CACHE>(kc, score, pos, m, k, sm);
   }
-  const int n_eq = sm->cnt;  // elements equal to the threshold; `rem` of them are taken
-  r.thr = prefix;
-  if (rem == n_eq) { r.pthr = 0xffffffffu; return r; }
-  // ties at the boundary: keep the `rem` smallest positions among the tied elements,
-  // i.e. select the rem-th largest of (~pos)
-  const uint64_t thr = prefix;
-  auto key2 = [&](int j, uint64_t* key) {
-    if ((uint64_t)__double_as_longlong(score(j)) != thr) return false;
-    *key = (uint64_t)(0xffffffffu - pos(j));
-    return true;
-  };
-  uint64_t p2 = 0, m2 = 0;
-  for (int shift = 24; shift >= 0; shift -= 8) {
-    fg_radix_pass(key2, m, shift, p2, m2, rem, sm);
-    p2 |= (uint64_t)sm->digit << shift;
-    m2 |= (uint64_t)0xff << shift;
-    rem = sm->rem;
-  }
-  r.pthr = 0xffffffffu - (uint32_t)p2;
-  return r;
+  const uint64_t none[1] = {0ull};
+  return fg_select_topk_impl<0>(none, score, pos, m, k, sm);
 }

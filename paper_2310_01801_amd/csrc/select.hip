@@ -156,14 +156,23 @@ __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restr
   }
 }
 
-// item_unit[c] = u for every split-KV work item c of unit u.
+// Work-item records of the decode attention kernel: item c of unit u covers slots
+// [256 * (c - chunk_off[u]), +256) of that unit. 8 ints per item: unit, chunk, cap, 1, off lo, off hi, 0, 0.
 __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restrict__ chunk_off,
-                                                          int32_t* __restrict__ item_unit,
+                                                          const int32_t* __restrict__ cap,
+                                                          const int64_t* __restrict__ off,
+                                                          int32_t* __restrict__ item_rec,
                                                           const int32_t* __restrict__ flags, int U) {
   if (flags[0] != 0) return;
   const int u = blockIdx.x * 256 + threadIdx.x;
   if (u >= U) return;
-  for (int c = chunk_off[u]; c < chunk_off[u + 1]; ++c) item_unit[c] = u;
+  const int64_t o = off[u];
+  const int c0 = chunk_off[u], c1 = chunk_off[u + 1];
+  for (int c = c0; c < c1; ++c) {
+    int32_t* r = item_rec + (size_t)c * 8;
+    r[0] = u; r[1] = c - c0; r[2] = cap[u]; r[3] = 1;
+    r[4] = (int32_t)(o & 0xffffffffll); r[5] = (int32_t)(o >> 32); r[6] = 0; r[7] = 0;
+  }
 }
 
 // 16 prompt positions per workgroup; 16-byte chunks of the kept rows are copied by
@@ -296,7 +305,7 @@ hipError_t fg_launch_offsets(const int32_t* cap, int64_t* off, int32_t* chunk_of
   hipLaunchKernelGGL(fg_offsets_kernel, dim3(1), dim3(1024), 0, s, cap, off, chunk_off, flags, U,
                      pool_tokens, max_chunks);
   hipLaunchKernelGGL(fg_item_map_kernel, dim3((unsigned)((U + 255) / 256)), dim3(256), 0, s,
-                     chunk_off, item_unit, flags, U);
+                     chunk_off, cap, off, item_unit, flags, U);
   return hipGetLastError();
 }
 
