@@ -31,6 +31,7 @@ def parse():
     ap.add_argument("--workload", default="llama7b_b1")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override S (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--forced-policy", type=int, default=-1, help="every unit uses this policy (non-adaptive baselines)")
     ap.add_argument("--cpu-sample-units", type=int, default=0, help="0 = sized for ~20 s")
     return ap.parse_args()
 
@@ -80,7 +81,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f)
+    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f, 0.0, args.forced_policy)
     workspace = torch.empty(binding.fastgen_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
 
     def one_pass(timing=False):

@@ -179,13 +179,15 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   constexpr int RB = D * ESIZE, CPR = RB / 16;
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
-  if (a.flags[0] != 0) return;
   const int u = blockIdx.x, tid = threadIdx.x;
-  const int Lold = a.len[u], L = Lold + 1;
-  if (L > a.cap[u]) return;
-  const int nch = (L + CH - 1) / CH;
-  const float* part = a.part + (size_t)a.chunk_off[u] * (D + 2);
+  // independent header loads first, then the checks
+  const int overflow = a.flags[0];
+  const int Lold = a.len[u], cap = a.cap[u], c_off = a.chunk_off[u], policy = a.policy[u];
   const int64_t off = a.off[u];
+  const int L = Lold + 1;
+  if (overflow != 0 || L > cap) return;
+  const int nch = (L + CH - 1) / CH;
+  const float* part = a.part + (size_t)c_off * (D + 2);
 
   // ---- merge the chunk partials: o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M)
   float M = FG_NEG_BIG;
@@ -201,7 +203,6 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     fg_store_out<ESIZE>(a.out, (size_t)u * D + tid, o * inv);
   }
 
-  const int policy = a.policy[u];
   if (policy >= 4) {
     if (tid == 0) a.len[u] = L;
     return;
@@ -222,20 +223,35 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   fg_topk tk;
   tk.mode = 0; tk.thr = 0; tk.pthr = 0;
   if (small) {
+    // all loads first (they are independent), then the arithmetic, then the stores
+    float lg[NC];
+    double sc[NC];
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
       const int j = tid + 256 * i;
       kc[i] = 0;
+      lg[i] = 0.f;
+      sc[i] = 0.0;
       if (j < L) {
         const int cb = cls[j];
         const int pj = pos[j];
         if ((cb & cmask) != 0 || pj > wlo) prot |= 1u << i;
         if (policy >= 2) {
+          lg[i] = a.clogit[off + j];
+          sc[i] = score[j];
+        }
+      }
+    }
+    if (policy >= 2) {
+#pragma unroll
+      for (int i = 0; i < NC; ++i) {
+        const int j = tid + 256 * i;
+        if (j < L) {
           // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
-          const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
-          const double sc = score[j] + (double)aj;
-          score[j] = sc;
-          kc[i] = (uint64_t)__double_as_longlong(sc);
+          const float aj = fg_exp2(lg[i] - M) * inv;
+          const double v = sc[i] + (double)aj;
+          score[j] = v;
+          kc[i] = (uint64_t)__double_as_longlong(v);
         }
       }
     }
@@ -287,7 +303,6 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
 
   // ---- in-place release: i-th hole (evicted slot below new_len) <- i-th kept slot above it
   int* scratch = reinterpret_cast<int*>(a.clogit + off);  // logits are dead from here on
-  const int cap = a.cap[u];
   __syncthreads();
   int run_h = 0, run_m = 0;
   if (small) {
@@ -341,19 +356,41 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const int moves = run_h;  // == run_m
   char* ck = static_cast<char*>(a.ck) + off * RB;
   char* cv = static_cast<char*>(a.cv) + off * RB;
-  for (int q = tid; q < moves * CPR; q += 256) {
-    const int i = q / CPR, ch = q % CPR;
-    const int dst = scratch[i], src = scratch[cap - 1 - i];
-    *reinterpret_cast<u32x4*>(ck + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(ck + (size_t)src * RB + ch * 16);
-    *reinterpret_cast<u32x4*>(cv + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(cv + (size_t)src * RB + ch * 16);
-  }
-  // the kept() predicate reads score/pos/cls: move them only after every thread is done with it
-  __syncthreads();
-  for (int i = tid; i < moves; i += 256) {
-    const int dst = scratch[i], src = scratch[cap - 1 - i];
-    score[dst] = score[src];
-    a.cpos[off + dst] = pos[src];
-    a.ccls[off + dst] = cls[src];
+  // the kept() predicate of the large-unit path reads score/pos/cls from memory: there the
+  // bookkeeping moves only after every thread is done with it
+  if (!small) {
+    for (int q = tid; q < moves * CPR; q += 256) {
+      const int i = q / CPR, ch = q % CPR;
+      const int dst = scratch[i], src = scratch[cap - 1 - i];
+      *reinterpret_cast<u32x4*>(ck + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(ck + (size_t)src * RB + ch * 16);
+      *reinterpret_cast<u32x4*>(cv + (size_t)dst * RB + ch * 16) = *reinterpret_cast<const u32x4*>(cv + (size_t)src * RB + ch * 16);
+    }
+    __syncthreads();
+    for (int i = tid; i < moves; i += 256) {
+      const int dst = scratch[i], src = scratch[cap - 1 - i];
+      score[dst] = score[src];
+      a.cpos[off + dst] = pos[src];
+      a.ccls[off + dst] = cls[src];
+    }
+  } else {
+    // rows and bookkeeping in one sweep: CPR lanes copy the row, one more moves score/pos/class
+    for (int q = tid; q < moves * (CPR + 1); q += 256) {
+      const int i = q / (CPR + 1), ch = q % (CPR + 1);
+      const int dst = scratch[i], src = scratch[cap - 1 - i];
+      if (ch < CPR) {
+        const u32x4 kr = *reinterpret_cast<const u32x4*>(ck + (size_t)src * RB + ch * 16);
+        const u32x4 vr = *reinterpret_cast<const u32x4*>(cv + (size_t)src * RB + ch * 16);
+        *reinterpret_cast<u32x4*>(ck + (size_t)dst * RB + ch * 16) = kr;
+        *reinterpret_cast<u32x4*>(cv + (size_t)dst * RB + ch * 16) = vr;
+      } else {
+        const double sv = score[src];
+        const int pv = pos[src];
+        const uint8_t cb = cls[src];
+        score[dst] = sv;
+        a.cpos[off + dst] = pv;
+        a.ccls[off + dst] = cb;
+      }
+    }
   }
   if (tid == 0) a.len[u] = new_len;
 }

@@ -31,6 +31,19 @@ __device__ __forceinline__ bool fg_in_topk(const fg_topk& t, double score, uint3
   return key > t.thr || (key == t.thr && pos <= t.pthr);
 }
 
+// hist[digit] += 1 for every lane with `active`; lanes sharing the digit of the first active
+// lane are counted with one atomic (keys cluster in few buckets during the first passes).
+__device__ __forceinline__ void fg_hist_add(int* hist, bool active, int digit) {
+  const unsigned long long act = __ballot(active);
+  if (act == 0ull) return;
+  const int leader = __ffsll((long long)act) - 1;
+  const int d0 = __shfl(digit, leader, 64);
+  const bool same = active && digit == d0;
+  const unsigned long long grp = __ballot(same);
+  if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d0], (int)__popcll(grp));
+  if (active && !same) atomicAdd(&hist[digit], 1);
+}
+
 // After the histogram of one digit is complete: locate the bucket that holds the rem-th
 // largest. Thread t looks at bucket 255 - t (descending order).
 __device__ __forceinline__ void fg_radix_locate(int rem, fg_select_smem* sm) {
@@ -99,7 +112,7 @@ __device__ __forceinline__ fg_topk fg_select_topk_impl(const uint64_t (&kc)[NC >
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
           const int j = tid + 256 * i;
-          if (j < m && (kc[i] & mask) == prefix) atomicAdd(&sm->hist[(int)((kc[i] >> shift) & 255u)], 1);
+          fg_hist_add(sm->hist, j < m && (kc[i] & mask) == prefix, (int)((kc[i] >> shift) & 255u));
         }
       } else {
         for (int j = tid; j < m; j += 256) {
