@@ -138,3 +138,30 @@ def test_llama7b_full_size_sampled_units():
     sample = sorted(rng.choice(w.num_units, size=12, replace=False).tolist())
     rep = H.compare(run, check_units=sample, state_steps=[0, 11, 23], check_rows=False)
     _report("llama7b_b1 full size, 12 sampled units", rep)
+
+
+# ---- the remaining BASELINE configurations at full size, oracle on a seeded sample of units.
+# The decode horizon is shortened (the step logic is covered above; these runs are about the
+# shapes, the ragged-length mix and the grid sizes of the large launches).
+
+def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0):
+    w = W[name].scaled(steps=steps) if T is None else W[name].scaled(steps=steps, T=T)
+    run = H.GpuRun(w, range(w.num_units))
+    rng = np.random.default_rng(seed)
+    sample = sorted(rng.choice(w.num_units, size=n_sample, replace=False).tolist())
+    rep = H.compare(run, check_units=sample, state_steps=state_steps or [0, steps - 1], check_rows=False)
+    _report(f"{name} full size (T={w.T}), {n_sample} sampled units, {steps} steps", rep)
+    return rep
+
+
+@pytest.mark.parametrize("T", [0.90, 0.98])
+def test_llama7b_b16_full_size_sampled_units(T):
+    _full_size("llama7b_b16", 12, 12, T=T, seed=16)
+
+
+def test_llama13b_b4_full_size_sampled_units():
+    _full_size("llama13b_b4", 6, 8, seed=13)
+
+
+def test_llama65b_b2_full_size_sampled_units():
+    _full_size("llama65b_b2", 4, 6, seed=65)
