@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--workload", default="llama7b_b1")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override S (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--forced-policy", type=int, default=-1, help="every unit uses this policy (non-adaptive baselines)")
     ap.add_argument("--cpu-sample-units", type=int, default=0, help="0 = sized for ~20 s")
     return ap.parse_args()
@@ -102,6 +104,12 @@ def main():
         fg.close()
         return res
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_pass()
     torch.cuda.synchronize()

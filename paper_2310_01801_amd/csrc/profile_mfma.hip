@@ -113,18 +113,22 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   // ---- per-lane running statistics
   float m_run[2] = {FG_NEG_BIG, FG_NEG_BIG}, l_run[2] = {0.f, 0.f};  // pass 1
   double col_acc[2] = {0.0, 0.0}, band_acc[2] = {0.0, 0.0};          // pass 2
-  bool snapped[2] = {false, false};
 
-  if (t_begin < t_end) {
-    gload(t_begin);
+  // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards, so that the
+  // workgroups of one unit stream the same tiles at the same time, measured 25 % slower).
+  const int n_it = t_end - t_begin;
+  auto tile_of = [&](int it) { return t_begin + it; };
+  if (n_it > 0) {
+    gload(tile_of(0));
     lstore(0);
   }
   __syncthreads();
 
-  for (int t = t_begin; t < t_end; ++t) {
-    const int buf = (t - t_begin) & 1;
+  for (int it = 0; it < n_it; ++it) {
+    const int buf = it & 1;
+    const int t = tile_of(it);
     const int t0 = t * kTile;
-    gload(min(t + 1, t_end - 1));  // unconditional: the load count per iteration is static
+    gload(tile_of(min(it + 1, n_it - 1)));  // unconditional: the load count per iteration is static
 
     // what this wave has to do with the tile, per owner fragment
     bool need[2];
@@ -203,15 +207,12 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
           const bool full = (t0 >= Cf + 31) && (t0 + 31 < n);
           const bool inside = (t0 + 31 - Cf) < w;   // every element within the local band
           const bool outside = (t0 - (Cf + 31)) >= w;
-          if (!inside && !snapped[f]) {
-            band_acc[f] = col_acc[f];
-            snapped[f] = true;
-          }
           if (full && (inside || outside)) {
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -ls[i]));
             col_acc[f] += (double)s;
+            if (inside) band_acc[f] += (double)s;  // the whole tile lies in the local band
           } else {
             const int dbase = sbase - col;        // row - col = dbase + (i>>2)*8 + (i&3)
             const int rlim = n - sbase;           // row < n  iff  (i>>2)*8 + (i&3) < rlim
@@ -226,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
               sb += (ok && dist < w) ? p : 0.f;
             }
             col_acc[f] += (double)s;
-            if (snapped[f]) band_acc[f] += (double)sb;
+            band_acc[f] += (double)sb;
           }
         }
       }
@@ -250,7 +251,6 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   } else {
 #pragma unroll
     for (int f = 0; f < 2; ++f) {
-      if (!snapped[f]) band_acc[f] = col_acc[f];
       const double cs = col_acc[f] + fg_shfl_xor_f64(col_acc[f], 32);
       const double bs = band_acc[f] + fg_shfl_xor_f64(band_acc[f], 32);
       const int col = O0 + 32 * f + ln;
