@@ -22,6 +22,15 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_MFMA = 2.5e15   # flop/s, dense, MI355X
 PEAK_HBM = 8.0e12         # B/s
 
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy of
+# known size (factors 2.00 / 1.00), for the default workload; see
+# profiles/hbm_traffic_llama7b_b1_pmc.md for the commands. Offline numbers: the counters cannot
+# be read inside a timed run.
+MEASURED_TRAFFIC = {
+    "llama7b_b1": {"sweeps": 1146e6 + 8.4e6 + 2217e6 + 33.6e6,   # both sweeps together
+                   "decode_attn": 540e6 + 7.8e6},                # first 16 decode steps, per launch
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -134,7 +143,8 @@ def main():
     mfma_achieved = 2 * flop_sweep / (sweeps_ms * 1e-3)
     roof_profile = dict(kernel="fg_profile_mfma_kernel (both sweeps)", bound="mfma",
                         achieved=mfma_achieved / 1e12, peak=PEAK_BF16_MFMA / 1e12, unit="TFLOP/s",
-                        frac=mfma_achieved / PEAK_BF16_MFMA, traffic=None,
+                        frac=mfma_achieved / PEAK_BF16_MFMA,
+                        traffic=MEASURED_TRAFFIC.get(w.name, {}).get("sweeps") if args.forced_policy < 0 else None,
                         avg_launch_ms=sweeps_ms / 2, flop_per_launch=flop_sweep)
 
     # ---- roofline of the decode attention kernel (HBM bound): one untimed replay logs lengths
@@ -159,7 +169,8 @@ def main():
         upd_ms = phase["decode_update"] / max(1, launches["decode_update"])
         bw = (attn_b / S) / (attn_ms * 1e-3)
         roof_decode = dict(kernel="fg_decode_partial_kernel", bound="hbm", achieved=bw / 1e9,
-                           peak=PEAK_HBM / 1e9, unit="GB/s", frac=bw / PEAK_HBM, traffic=None,
+                           peak=PEAK_HBM / 1e9, unit="GB/s", frac=bw / PEAK_HBM,
+                           traffic=MEASURED_TRAFFIC.get(w.name, {}).get("decode_attn") if args.forced_policy < 0 else None,
                            avg_launch_ms=attn_ms, bytes_per_launch=attn_b / S,
                            update_kernel_avg_ms=upd_ms,
                            whole_step_GBps=(step_b / S) / ((attn_ms + upd_ms) * 1e-3) / 1e9,
