@@ -86,19 +86,28 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
     t_end = (n + kTile - 1) / kTile;
   }
 
+  // Streamed tiles come through raw buffer loads: the per-thread byte offset is fixed, the
+  // tile offset is a scalar, and rows past the end of the unit read as zeros (every use of
+  // them is masked), so a load costs no vector-ALU instruction.
+  const __amdgpu_buffer_rsrc_t str_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(str_mat), 0, n * D * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t lse_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_row), 0, n * 4, 0x00020000);
+  int voff[LOADS];
+#pragma unroll
+  for (int r = 0; r < LOADS; ++r) {
+    const int q = tid + 256 * r;
+    voff[r] = (q / CHUNKS_PER_ROW) * (D * 2) + (q % CHUNKS_PER_ROW) * 16;
+  }
+  const int voff_lse = (tid & (kTile - 1)) * 4;
   u32x4 stage[LOADS];
   float stage_lse = 0.f;
   auto gload = [&](int t) {
     const int t0 = t * kTile;
 #pragma unroll
-    for (int r = 0; r < LOADS; ++r) {
-      const int q = tid + 256 * r;
-      const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
-      // rows past the end repeat the last row; every use of them is masked (causal / tail)
-      const int row = min(t0 + item, n - 1);
-      stage[r] = *reinterpret_cast<const u32x4*>(str_mat + (size_t)row * D + ch * 8);
-    }
-    if (PASS == 2) stage_lse = lse_row[min(t0 + (tid & (kTile - 1)), n - 1)];
+    for (int r = 0; r < LOADS; ++r)
+      stage[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(str_rsrc, voff[r], t0 * (D * 2), 0));
+    if (PASS == 2) stage_lse = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lse_rsrc, voff_lse, t0 * 4, 0));
   };
   auto lstore = [&](int buf) {
 #pragma unroll
@@ -162,10 +171,13 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
           const int Of = O0 + 32 * f;
           const int row = Of + ln;
           if (t0 + 31 <= Of) {  // every column of the tile is visible to every row
-            float tmax = acc[f][0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, acc[f][i]);
-            const float m_new = fmaxf(m_run[f], tmax * c);  // c > 0
+            // 16 values -> 8 three-operand maxima (c > 0: the max of the raw dot products is enough)
+            const f32x16& ac = acc[f];
+            const float x0 = fmaxf(fmaxf(ac[0], ac[1]), ac[2]), x1 = fmaxf(fmaxf(ac[3], ac[4]), ac[5]);
+            const float x2 = fmaxf(fmaxf(ac[6], ac[7]), ac[8]), x3 = fmaxf(fmaxf(ac[9], ac[10]), ac[11]);
+            const float x4 = fmaxf(fmaxf(ac[12], ac[13]), ac[14]);
+            const float y0 = fmaxf(fmaxf(x0, x1), x2), y1 = fmaxf(fmaxf(x3, x4), ac[15]);
+            const float m_new = fmaxf(fmaxf(y0, y1) * c, m_run[f]);
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
