@@ -165,3 +165,29 @@ def test_llama13b_b4_full_size_sampled_units():
 
 def test_llama65b_b2_full_size_sampled_units():
     _full_size("llama65b_b2", 4, 6, seed=65)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(T=1.0),                 # only C_full can recover everything
+    dict(r_f=0.0),               # frequent budget 0: policy 2 == policy 1
+    dict(r_l=0.0),               # window clamps to 1 token
+    dict(r_f=1.0, r_l=1.0),      # budgets cover everything: policy 2 keeps all tokens
+    dict(T=0.5),
+])
+def test_hyper_parameter_edges(kw):
+    w = W["llama7b_b1"].scaled(name="edges", layers=1, heads=10, batch=2, prompt_len=160, steps=10, seed=21, **kw)
+    run = H.GpuRun(w, range(w.num_units))
+    rep = H.compare(run)
+    _report(f"edges {kw}", rep)
+    if kw.get("T") == 1.0:
+        assert set(rep.policies) <= {2, 3, 4}   # a policy below full only if it keeps every token
+
+
+def test_no_special_tokens_rows_without_kept_tokens():
+    """A prompt without any special token: policy 0 keeps nothing from the prompt, the new
+    token alone is attended at the first decode step (softmax over one element)."""
+    w = W["llama7b_b1"].scaled(name="nospecial", layers=1, heads=6, batch=1, prompt_len=96, steps=6, seed=22)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=0)
+    run.cls_u &= 2          # drop the special bit everywhere (both sides read these classes)
+    rep = H.compare(run)
+    _report("no special tokens, forced policy 0", rep)
