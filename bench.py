@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--cache-tokens", type=int, default=0, help="cache pool capacity in tokens (0 = worst case)")
     ap.add_argument("--forced-policy", type=int, default=-1, help="every unit uses this policy (non-adaptive baselines)")
     ap.add_argument("--cpu-sample-units", type=int, default=0, help="0 = sized for ~20 s")
     return ap.parse_args()
@@ -92,7 +93,7 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f, 0.0, args.forced_policy)
+    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f, 0.0, args.forced_policy, args.cache_tokens)
     workspace = torch.empty(binding.fastgen_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
 
     def one_pass(timing=False):

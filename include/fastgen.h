@@ -65,6 +65,13 @@ enum {
 /* Token-class byte: which tokens C_special / C_punct. keep (Sec. 3.4). */
 enum { FG_CLASS_SPECIAL = 1, FG_CLASS_PUNCT = 2 };
 
+/* Components a hybrid policy is the union of (Sec. 3.4). cfg.family[c] is the component
+ * mask of policy id c = 0..3; id 4 is always C_full. The default family is Eq. 2's:
+ * {SPECIAL, SPECIAL|PUNCT, SPECIAL|PUNCT|FREQUENT, SPECIAL|PUNCT|FREQUENT|LOCAL}. Other
+ * tables give the ablations of App. A.1 (a component left out, components added in another
+ * order) and, with forced_policy, the fixed single-policy baselines of Sec. 5.1. */
+enum { FG_COMP_SPECIAL = 1, FG_COMP_PUNCT = 2, FG_COMP_FREQUENT = 4, FG_COMP_LOCAL = 8 };
+
 typedef struct {
   int32_t num_units;      /* U = sequences * layers * heads, > 0                              */
   int32_t num_seqs;       /* B; must divide U; unit u belongs to sequence u / (U / B)         */
@@ -76,9 +83,12 @@ typedef struct {
   double r_l;             /* local window  w = max(1, floor(r_l * n))   (ratio of INPUT len)  */
   double r_f;             /* frequent budget k_f(L) = floor(r_f * L)    (ratio of CURRENT len)*/
   float softmax_scale;    /* logits = scale * q.k ; 0 selects 1/sqrt(head_dim)                */
-  int32_t forced_policy;  /* -1: adaptive (Eq. 1); 0..4: every unit uses this policy          */
+  int32_t forced_policy;  /* -1: adaptive (Eq. 1); 0..4: every unit uses this (usable) policy */
   int64_t cache_tokens;   /* capacity of the cache pool in tokens summed over all units;
                              0 selects the worst case U * (n + S)                             */
+  int32_t family[4];      /* FG_COMP_* mask of policy ids 0..3; all zero selects Eq. 2's
+                             family; otherwise a zero entry is an unused id. Eq. 1 takes the
+                             cheapest usable policy reaching T (equal cost: smaller id)       */
 } fg_config;
 
 /* Size in bytes of the device workspace a context with this configuration needs

@@ -53,6 +53,13 @@ N_POLICIES = 5
 CLASS_SPECIAL = 1
 CLASS_PUNCT = 2
 
+# A policy family is four component masks plus C_full (policy id 4). Components (Sec. 3.4):
+# bit 0 special, bit 1 punctuation, bit 2 frequent, bit 3 local; mask 0 = slot not used.
+# The default is the family of Eq. 2; App. A.1 (Tables 4 and 5) varies the members and the
+# order in which components are added, and Sec. 5.1 uses single members as fixed baselines.
+SPECIAL, PUNCT, FREQUENT, LOCAL = 1, 2, 4, 8
+DEFAULT_FAMILY = (SPECIAL, SPECIAL | PUNCT, SPECIAL | PUNCT | FREQUENT, SPECIAL | PUNCT | FREQUENT | LOCAL)
+
 
 # ----------------------------------------------------------------------------------------
 # budgets (Sec. 3.4: ratios r_l, r_f)
@@ -121,20 +128,31 @@ class Profile:
     sets: List[np.ndarray] = field(default_factory=list)  # K_0..K_4 (sorted positions)
 
 
-def kept_sets(cls: np.ndarray, colsum: np.ndarray, r_l: float, r_f: float) -> List[np.ndarray]:
-    """K_0..K_4 at the end of the prompt: unions in the order of Eq. 2."""
+def component_sets(cls: np.ndarray, colsum: np.ndarray, r_l: float, r_f: float) -> Dict[int, np.ndarray]:
+    """The four base kept sets at the end of the prompt (Sec. 3.4)."""
     n = colsum.size
     pos = np.arange(n, dtype=np.int64)
-    special = pos[(cls & CLASS_SPECIAL) != 0]
-    punct = pos[(cls & CLASS_PUNCT) != 0]
-    freq = top_k_positions(colsum, pos, frequent_budget(r_f, n))
     w = local_window(r_l, n)
-    local = pos[max(0, n - w):]
-    K0 = special
-    K1 = np.union1d(K0, punct)
-    K2 = np.union1d(K1, freq)
-    K3 = np.union1d(K2, local)
-    return [K0, K1, K2, K3, pos]
+    return {SPECIAL: pos[(cls & CLASS_SPECIAL) != 0],
+            PUNCT: pos[(cls & CLASS_PUNCT) != 0],
+            FREQUENT: top_k_positions(colsum, pos, frequent_budget(r_f, n)),
+            LOCAL: pos[max(0, n - w):]}
+
+
+def kept_sets(cls: np.ndarray, colsum: np.ndarray, r_l: float, r_f: float,
+              family=DEFAULT_FAMILY) -> List[np.ndarray]:
+    """K_0..K_4 at the end of the prompt: "+" is the union of the components' kept sets."""
+    n = colsum.size
+    comp = component_sets(cls, colsum, r_l, r_f)
+    out = []
+    for mask in family:
+        k = np.zeros(0, dtype=np.int64)
+        for bit in (SPECIAL, PUNCT, FREQUENT, LOCAL):
+            if mask & bit:
+                k = np.union1d(k, comp[bit])
+        out.append(k)
+    out.append(np.arange(n, dtype=np.int64))
+    return out
 
 
 def recovery_dense(A: np.ndarray, static_keep: np.ndarray, window: int) -> float:
@@ -150,10 +168,12 @@ def recovery_dense(A: np.ndarray, static_keep: np.ndarray, window: int) -> float
     return float(kept_mass_per_row.mean())
 
 
-def select_policy(cost: np.ndarray, recovery: np.ndarray, T: float) -> int:
+def select_policy(cost: np.ndarray, recovery: np.ndarray, T: float, usable=None) -> int:
     """Eq. 1: argmin cost subject to recovery >= T; equal cost -> smaller id."""
     best = -1
     for c in range(N_POLICIES):
+        if usable is not None and not usable[c]:
+            continue
         # C_full is the uncompressed cache: its difference to A is zero by definition
         feasible = (c == N_POLICIES - 1) or (recovery[c] >= T)
         if feasible and (best < 0 or cost[c] < cost[best]):
@@ -162,24 +182,34 @@ def select_policy(cost: np.ndarray, recovery: np.ndarray, T: float) -> int:
 
 
 def profile_unit(Q: np.ndarray, K: np.ndarray, cls: np.ndarray, T: float, r_l: float,
-                 r_f: float, scale: float, forced_policy: int = -1) -> Profile:
+                 r_f: float, scale: float, forced_policy: int = -1, family=DEFAULT_FAMILY) -> Profile:
     """Alg. 1 up to the choice of C for one head."""
     A = attention_map(Q, K, scale)
     n = A.shape[0]
     colsum = A.sum(axis=0)
-    sets = kept_sets(np.asarray(cls), colsum, r_l, r_f)
+    cls = np.asarray(cls)
+    sets = kept_sets(cls, colsum, r_l, r_f, family)
+    comp = component_sets(cls, colsum, r_l, r_f)
     w = local_window(r_l, n)
     rec = np.zeros(N_POLICIES)
+    usable = [m != 0 for m in family] + [True]
     for c in range(N_POLICIES):
-        mask = np.zeros(n, dtype=bool)
-        # the static part of K_3 is K_2: its local component is row-relative
-        mask[sets[min(c, 2)] if c < 4 else sets[4]] = True
-        rec[c] = recovery_dense(A, mask, w if c == 3 else 0)
+        static = np.zeros(n, dtype=bool)
+        if c == 4:
+            static[:] = True
+            rec[c] = recovery_dense(A, static, 0)
+            continue
+        # the local component is row-relative on the prompt; the others are static column sets
+        for bit in (SPECIAL, PUNCT, FREQUENT):
+            if family[c] & bit:
+                static[comp[bit]] = True
+        rec[c] = recovery_dense(A, static, w if family[c] & LOCAL else 0)
     cost = np.array([s.size for s in sets], dtype=np.int64)
-    policy = select_policy(cost, rec, T) if forced_policy < 0 else int(forced_policy)
+    policy = select_policy(cost, rec, T, usable) if forced_policy < 0 else int(forced_policy)
+    margins = [abs(rec[c] - T) for c in range(4) if usable[c]]
     return Profile(policy=policy, recovery=rec, cost=cost, kept=sets[policy], colsum=colsum,
                    window=w, k_f=frequent_budget(r_f, n),
-                   margin=float(np.min(np.abs(rec[:4] - T))),
+                   margin=float(min(margins)) if margins else math.inf,
                    topk_gap=boundary_gap(colsum, frequent_budget(r_f, n)), sets=sets)
 
 
@@ -197,31 +227,35 @@ class Cache:
     score: np.ndarray           # [len] cumulative attention score
     pos: np.ndarray             # [len] int64
     cls: np.ndarray             # [len] uint8
+    mask: int = 0               # component mask of the policy (ignored for C_full)
     min_gap: float = math.inf   # smallest relative top-k boundary gap seen while decoding
     fragile_step: int = -1      # first decode step whose boundary gap fell below `gap_eps`
 
 
-def compact_unit(K: np.ndarray, V: np.ndarray, cls: np.ndarray, prof: Profile) -> Cache:
+def compact_unit(K: np.ndarray, V: np.ndarray, cls: np.ndarray, prof: Profile,
+                 family=DEFAULT_FAMILY) -> Cache:
     keep = prof.kept
-    return Cache(policy=prof.policy, n=K.shape[0],
+    return Cache(policy=prof.policy, n=K.shape[0], mask=family[prof.policy] if prof.policy < 4 else 0,
                  K=np.asarray(K, dtype=np.float64)[keep].copy(),
                  V=np.asarray(V, dtype=np.float64)[keep].copy(),
                  score=prof.colsum[keep].copy(), pos=keep.copy(),
                  cls=np.asarray(cls, dtype=np.uint8)[keep].copy())
 
 
-def kept_after_step(policy: int, pos: np.ndarray, cls: np.ndarray, score: np.ndarray,
+def kept_after_step(policy: int, mask: int, pos: np.ndarray, cls: np.ndarray, score: np.ndarray,
                     p_new: int, window: int, r_f: float) -> np.ndarray:
     """Boolean mask over held tokens: which stay after the token at position p_new."""
     if policy == 4:
         return np.ones(pos.size, dtype=bool)
-    keep = (cls & CLASS_SPECIAL) != 0
-    if policy >= 1:
+    keep = np.zeros(pos.size, dtype=bool)
+    if mask & SPECIAL:
+        keep |= (cls & CLASS_SPECIAL) != 0
+    if mask & PUNCT:
         keep |= (cls & CLASS_PUNCT) != 0
-    if policy >= 2:
+    if mask & FREQUENT:
         top = top_k_positions(score, pos, frequent_budget(r_f, p_new + 1))
         keep |= np.isin(pos, top)
-    if policy >= 3:
+    if mask & LOCAL:
         keep |= pos > p_new - window
     return keep
 
@@ -239,22 +273,23 @@ def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, c
     e = np.exp(s - s.max())
     a = e / e.sum()
     o = a @ c.V
-    if c.policy in (2, 3):
+    if c.policy < 4 and (c.mask & FREQUENT):
         c.score = c.score + a
         g = boundary_gap(c.score, frequent_budget(r_f, p + 1))
         c.min_gap = min(c.min_gap, g)
         if g < gap_eps and c.fragile_step < 0:
             c.fragile_step = t
-    keep = kept_after_step(c.policy, c.pos, c.cls, c.score, p, local_window(r_l, c.n), r_f)
+    keep = kept_after_step(c.policy, c.mask, c.pos, c.cls, c.score, p, local_window(r_l, c.n), r_f)
     c.K, c.V, c.score, c.pos, c.cls = c.K[keep], c.V[keep], c.score[keep], c.pos[keep], c.cls[keep]
     return o
 
 
 def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, scale,
-             forced_policy: int = -1, gap_eps: float = 0.0, record_states: bool = False) -> Dict:
+             forced_policy: int = -1, gap_eps: float = 0.0, record_states: bool = False,
+             family=DEFAULT_FAMILY) -> Dict:
     """Whole path for one head: profile, compact, S decode steps."""
-    prof = profile_unit(Q, K, cls, T, r_l, r_f, scale, forced_policy)
-    cache = compact_unit(K, V, cls, prof)
+    prof = profile_unit(Q, K, cls, T, r_l, r_f, scale, forced_policy, family)
+    cache = compact_unit(K, V, cls, prof, family)
     S = 0 if q_steps is None else len(q_steps)
     d = np.asarray(K).shape[1]
     outs = np.zeros((S, d))

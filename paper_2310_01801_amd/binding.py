@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libfastgen.so")
 
 FG_OK, FG_EINVAL, FG_ENOMEM, FG_EHIP, FG_ESTATE, FG_ECAP = range(6)
 FG_F32, FG_BF16 = 0, 1
+FG_COMP_SPECIAL, FG_COMP_PUNCT, FG_COMP_FREQUENT, FG_COMP_LOCAL = 1, 2, 4, 8
 STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_ECAP")
 
 EXPORTED = (
@@ -33,7 +34,7 @@ class FgConfig(ctypes.Structure):
         ("dtype", ctypes.c_int32), ("prompt_len", ctypes.c_int32), ("max_new_tokens", ctypes.c_int32),
         ("T", ctypes.c_double), ("r_l", ctypes.c_double), ("r_f", ctypes.c_double),
         ("softmax_scale", ctypes.c_float), ("forced_policy", ctypes.c_int32),
-        ("cache_tokens", ctypes.c_int64),
+        ("cache_tokens", ctypes.c_int64), ("family", ctypes.c_int32 * 4),
     ]
 
 
@@ -93,10 +94,12 @@ def _stream() -> int:
 
 def make_config(num_units: int, num_seqs: int, head_dim: int, dtype: torch.dtype, prompt_len: int,
                 max_new_tokens: int, T: float, r_l: float, r_f: float, softmax_scale: float = 0.0,
-                forced_policy: int = -1, cache_tokens: int = 0) -> FgConfig:
+                forced_policy: int = -1, cache_tokens: int = 0, family=None) -> FgConfig:
+    """family: None (the family of Eq. 2) or four FG_COMP_* masks for policy ids 0..3."""
     code = {torch.float32: FG_F32, torch.bfloat16: FG_BF16}[dtype]
+    fam = (ctypes.c_int32 * 4)(*(family if family is not None else (0, 0, 0, 0)))
     return FgConfig(num_units, num_seqs, head_dim, code, prompt_len, max_new_tokens, T, r_l, r_f,
-                    softmax_scale, forced_policy, cache_tokens)
+                    softmax_scale, forced_policy, cache_tokens, fam)
 
 
 def fastgen_workspace_bytes(cfg: FgConfig) -> int:

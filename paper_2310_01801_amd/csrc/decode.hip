@@ -182,7 +182,10 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const int u = blockIdx.x, tid = threadIdx.x;
   // independent header loads first, then the checks
   const int overflow = a.flags[0];
-  const int Lold = a.len[u], cap = a.cap[u], c_off = a.chunk_off[u], policy = a.policy[u];
+  const int Lold = a.len[u], cap = a.cap[u], c_off = a.chunk_off[u], pword = a.policy[u];
+  // policy word: id in the low byte, the policy's component mask (FG_COMP_*) above it
+  const int policy = pword & 0xff, comp = pword >> 8;
+  const bool freq = (comp & FG_COMP_FREQUENT) != 0;
   const int64_t off = a.off[u];
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
@@ -211,8 +214,8 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   double* score = a.cscore + off;
   const int32_t* pos = a.cpos + off;
   const uint8_t* cls = a.ccls + off;
-  const int cmask = FG_CLASS_SPECIAL | (policy >= 1 ? FG_CLASS_PUNCT : 0);
-  const int wlo = (policy >= 3) ? p_new - a.w : 0x7fffffff;  // positions above wlo are inside the window
+  const int cmask = ((comp & FG_COMP_SPECIAL) ? FG_CLASS_SPECIAL : 0) | ((comp & FG_COMP_PUNCT) ? FG_CLASS_PUNCT : 0);
+  const int wlo = (comp & FG_COMP_LOCAL) ? p_new - a.w : 0x7fffffff;  // positions above wlo are inside the window
 
   // Fast path (L <= 256 * NC): each thread keeps its slots' updated scores and a "protected"
   // bit (special / punctuation / window) in registers, so every later phase is register-only.
@@ -236,13 +239,13 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         const int cb = cls[j];
         const int pj = pos[j];
         if ((cb & cmask) != 0 || pj > wlo) prot |= 1u << i;
-        if (policy >= 2) {
+        if (freq) {
           lg[i] = a.clogit[off + j];
           sc[i] = score[j];
         }
       }
     }
-    if (policy >= 2) {
+    if (freq) {
 #pragma unroll
       for (int i = 0; i < NC; ++i) {
         const int j = tid + 256 * i;
@@ -255,13 +258,13 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         }
       }
     }
-    if (policy >= 2) {
+    if (freq) {
       const int k_f = fg_budget(a.r_f, p_new + 1);
       __syncthreads();  // score[] is re-read by other threads only if the boundary value is tied
       tk = fg_select_topk_regs<NC>(kc, [&](int j) { return score[j]; },
                                    [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
     }
-  } else if (policy >= 2) {
+  } else if (freq) {
     for (int j = tid; j < L; j += 256) {
       const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
       score[j] += (double)aj;
@@ -273,7 +276,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const bool tie_pos = (tk.mode == 2 && tk.pthr != 0xffffffffu);  // rare: boundary value shared
   auto kept = [&](int j) -> bool {  // from memory (large units and the tied case)
     bool k = (cls[j] & cmask) != 0 || pos[j] > wlo;
-    if (policy >= 2) k = k || fg_in_topk(tk, score[j], (uint32_t)pos[j]);
+    if (freq) k = k || fg_in_topk(tk, score[j], (uint32_t)pos[j]);
     return k;
   };
   uint32_t keepbits = 0;  // fast path: bit i = slot tid + 256 i stays
@@ -284,7 +287,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
       const int j = tid + 256 * i;
       if (j < L) {
         bool k = (prot >> i) & 1u;
-        if (policy >= 2 && !k) {
+        if (freq && !k) {
           if (tk.mode == 1) k = true;
           else if (tk.mode == 2) k = tie_pos ? fg_in_topk(tk, __longlong_as_double((long long)kc[i]), (uint32_t)pos[j])
                                              : (kc[i] >= tk.thr);

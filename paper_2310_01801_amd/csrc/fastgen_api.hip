@@ -35,6 +35,13 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
   FG_REQUIRE(c->softmax_scale >= 0.f && isfinite(c->softmax_scale), "softmax_scale must be >= 0");
   FG_REQUIRE(c->forced_policy >= -1 && c->forced_policy <= 4, "forced_policy must be -1..4");
   FG_REQUIRE(c->cache_tokens >= 0, "cache_tokens must be >= 0");
+  bool any = false;
+  for (int i = 0; i < 4; ++i) {
+    FG_REQUIRE(c->family[i] >= 0 && c->family[i] <= 15, "family entries must be FG_COMP_* masks (0..15)");
+    any = any || c->family[i] != 0;
+  }
+  FG_REQUIRE(!any || c->forced_policy < 0 || c->forced_policy == 4 || c->family[c->forced_policy] != 0,
+             "forced_policy names an unused family entry");
 #undef FG_REQUIRE
   return true;
 }
@@ -220,6 +227,13 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
   sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f;
   sa.forced_policy = c.forced_policy;
+  {
+    const bool any = c.family[0] || c.family[1] || c.family[2] || c.family[3];
+    const int eq2[4] = {FG_COMP_SPECIAL, FG_COMP_SPECIAL | FG_COMP_PUNCT,
+                        FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT,
+                        FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT | FG_COMP_LOCAL};
+    for (int i = 0; i < 4; ++i) sa.family[i] = any ? c.family[i] : eq2[i];
+  }
   {
     PhaseTimer tm(ctx, FG_PHASE_SELECT, s);
     e = fg_launch_select(sa, s);

@@ -76,6 +76,7 @@ struct fg_select_args {
   int U, n, units_per_seq, w, S;
   double T, r_f;
   int forced_policy;
+  int family[4];  // FG_COMP_* mask of policy ids 0..3 (0 = unused id)
 };
 
 struct fg_compact_args {

@@ -1,10 +1,10 @@
 // Policy choice and compaction (Alg. 1: "C <- apply Eq. 1 to A", "K^,V^ <- f(K,V,C)").
 //
-//   fg_select_kernel   per unit: the kept sets of the policy family of Eq. 2 (special,
-//                      +punctuation, +frequent, +local; "+" = union), their recoveries from
-//                      the column / band sums, the cheapest policy reaching T (Eq. 1; the
-//                      kept sets are nested, so the first policy in Eq. 2's order that
-//                      reaches T is the argmin), kept flags and their prefix scan.
+//   fg_select_kernel   per unit: the kept sets of the policy family (by default Eq. 2's:
+//                      special, +punctuation, +frequent, +local; "+" = union; any table of
+//                      component masks is accepted), their recoveries from the column /
+//                      band sums, the cheapest policy reaching T (Eq. 1), kept flags and
+//                      their prefix scan.
 //   fg_offsets_kernel  exclusive scan of the per-unit slot reservations -> pool offsets,
 //                      and the static split-KV work list of the decode kernels.
 //   fg_gather_kernel   copies the kept rows of K, V with score, position, class.
@@ -29,33 +29,43 @@ __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
   const fg_topk tk = fg_select_topk([&](int j) { return cs[j]; },
                                     [&](int j) { return (uint32_t)j; }, n, k_f, &sm);
 
+  // Recovery of a policy = mean over rows of the kept attention mass. A column in the
+  // policy's static set (special / punctuation / frequent) counts in every row: its column
+  // sum; any other column is only seen through the local band, if the policy has one.
   double r[4] = {0.0, 0.0, 0.0, 0.0};
-  int cnt[4] = {0, 0, 0, 0};
+  int cnt[4] = {0, 0, 0, 0}, ccnt[4] = {0, 0, 0, 0};
   for (int j = tid; j < n; j += 256) {
     const int c = cls[j];
-    const double s = cs[j];
-    const bool k0 = (c & FG_CLASS_SPECIAL) != 0;
-    const bool k1 = k0 || (c & FG_CLASS_PUNCT) != 0;
-    const bool k2 = k1 || fg_in_topk(tk, s, (uint32_t)j);
-    const bool k3 = k2 || (j >= n - w);
-    if (k0) { r[0] += s; cnt[0]++; }
-    if (k1) { r[1] += s; cnt[1]++; }
-    if (k2) { r[2] += s; cnt[2]++; }
-    r[3] += k2 ? s : bc[j];  // a column outside the static set is only seen through the local band
-    if (k3) cnt[3]++;
+    const double s = cs[j], b = bc[j];
+    const bool top = fg_in_topk(tk, s, (uint32_t)j), tail = j >= n - w;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int m = a.family[p];
+      const bool byclass = ((m & FG_COMP_SPECIAL) && (c & FG_CLASS_SPECIAL)) ||
+                           ((m & FG_COMP_PUNCT) && (c & FG_CLASS_PUNCT));
+      const bool st = byclass || ((m & FG_COMP_FREQUENT) && top);
+      const bool loc = (m & FG_COMP_LOCAL) != 0;
+      r[p] += st ? s : (loc ? b : 0.0);
+      if (st || (loc && tail)) cnt[p]++;
+      if (byclass) ccnt[p]++;
+    }
   }
   double R[5];
-  int C[5];
+  int C[5], CC[4];
   for (int c = 0; c < 4; ++c) {
     R[c] = fg_block_sum_f64(r[c], dred) / (double)n;
     C[c] = fg_block_sum_i32(cnt[c], ired);
+    CC[c] = fg_block_sum_i32(ccnt[c], ired);
   }
   R[4] = 1.0;
   C[4] = n;
+  // Eq. 1: the cheapest usable policy whose recovery reaches T; equal cost -> smaller id.
+  // C_full always qualifies. (For the nested family of Eq. 2 this is the first id reaching T.)
   int policy = 4;
   for (int c = 3; c >= 0; --c)
-    if (R[c] >= a.T) policy = c;
+    if (a.family[c] != 0 && R[c] >= a.T && C[c] <= C[policy]) policy = c;
   if (a.forced_policy >= 0) policy = a.forced_policy;
+  const int comp = policy < 4 ? a.family[policy] : 0;
 
   // kept flags of the chosen policy and their exclusive scan (slot of each kept token)
   int running = 0;
@@ -64,11 +74,11 @@ __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
     int keep = 0, cbyte = 0;
     if (j < n) {
       const int c = cls[j];
-      bool k = (c & FG_CLASS_SPECIAL) != 0;
-      if (policy >= 1) k = k || (c & FG_CLASS_PUNCT) != 0;
-      if (policy >= 2) k = k || fg_in_topk(tk, cs[j], (uint32_t)j);
-      if (policy >= 3) k = k || (j >= n - w);
-      if (policy >= 4) k = true;
+      bool k = policy >= 4;
+      if (comp & FG_COMP_SPECIAL) k = k || (c & FG_CLASS_SPECIAL) != 0;
+      if (comp & FG_COMP_PUNCT) k = k || (c & FG_CLASS_PUNCT) != 0;
+      if (comp & FG_COMP_FREQUENT) k = k || fg_in_topk(tk, cs[j], (uint32_t)j);
+      if (comp & FG_COMP_LOCAL) k = k || (j >= n - w);
       keep = k ? 1 : 0;
       cbyte = k ? (4 | (c & 3)) : 0;  // kept flag plus the token's class bits
     }
@@ -83,22 +93,26 @@ __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
   }
 
   if (tid == 0) {
-    // slots to reserve: every later token may be special/punctuation and stay (+S); the
-    // frequent budget follows the sequence length; the window is fixed; one extra slot for
-    // the new token while it is attended to. Never more than the uncompressed cache.
+    // slots to reserve: the class-kept prompt tokens, and if a class component is present
+    // every later token may be special/punctuation and stay (+S); the frequent budget follows
+    // the sequence length; the window is fixed; one extra slot for the new token while it is
+    // attended to. Never more than the uncompressed cache.
     const int S = a.S, full = n + S;
     long long cap;
     if (policy == 4) cap = full;
-    else if (policy <= 1) cap = (long long)C[policy] + S;
     else {
-      cap = (long long)C[1] + S + fg_budget(a.r_f, full) + 1;
-      if (policy == 3) cap += w;
+      cap = CC[policy];
+      if (comp & (FG_COMP_SPECIAL | FG_COMP_PUNCT)) cap += S;
+      if (comp & FG_COMP_FREQUENT) cap += fg_budget(a.r_f, full);
+      if (comp & FG_COMP_LOCAL) cap += w;
+      if (comp & (FG_COMP_FREQUENT | FG_COMP_LOCAL)) cap += 1;
+      if (cap < running) cap = running;
     }
     if (cap > full) cap = full;
     if (cap < 1) cap = 1;
     a.cap[u] = (int)cap;
     a.len[u] = running;
-    a.policy[u] = policy;
+    a.policy[u] = policy | (comp << 8);  // id in the low byte, component mask above
     if (a.policy_out) a.policy_out[u] = policy;
     for (int c = 0; c < 5; ++c) {
       a.recov[u * 5 + c] = R[c];

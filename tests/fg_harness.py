@@ -58,7 +58,8 @@ class GpuRun:
     """The HIP path on a list of units of a workload (each unit carries its own class row)."""
 
     def __init__(self, w: synth.Workload, units: Sequence[int], device="cuda:0",
-                 forced_policy: int = -1, gen_device: Optional[str] = None, cache_tokens: int = 0):
+                 forced_policy: int = -1, gen_device: Optional[str] = None, cache_tokens: int = 0,
+                 family: Optional[Sequence[int]] = None):
         self.w, self.units, self.device = w, list(units), device
         gen_device = gen_device or device
         self.plan = synth.unit_plan(w)
@@ -73,9 +74,10 @@ class GpuRun:
             self.q, self.k, self.v = (t.to(device) for t in
                                       synth.decode_batch(w, self.plan, self.cls_decode, self.units, gen_device))
         cfg = binding.make_config(m, m, w.head_dim, w.torch_dtype, w.prompt_len, w.steps, w.T, w.r_l,
-                                  w.r_f, 0.0, forced_policy, cache_tokens)
+                                  w.r_f, 0.0, forced_policy, cache_tokens, family)
         self.fg = binding.FastGen(cfg, device)
         self.forced = forced_policy
+        self.family = tuple(family) if family is not None else fo.DEFAULT_FAMILY
 
     def profile_and_compact(self):
         pol, rec, cnt = self.fg.fastgen_profile(self.Q, self.K, self.cls_u)
@@ -112,7 +114,7 @@ def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states:
     else:
         dec = (None, None, None, None)
     return fo.run_unit(*args, *dec, w.T, w.r_l, w.r_f, scale_of(w), forced_policy=run.forced,
-                       gap_eps=GAP_EPS, record_states=record_states)
+                       gap_eps=GAP_EPS, record_states=record_states, family=run.family)
 
 
 def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Optional[int] = None,
@@ -142,10 +144,11 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
             continue
         assert pol[i] == p.policy, f"unit {run.units[i]}: policy {pol[i]} vs oracle {p.policy} R={p.recovery}"
         tie = p.topk_gap < GAP_EPS or _abs_tie(p.colsum, p.k_f)
-        assert list(cnt[i][:2]) == list(p.cost[:2]) and cnt[i][4] == p.cost[4]
+        nofreq = [c for c in range(4) if not run.family[c] & fo.FREQUENT] + [4]
+        assert [cnt[i][c] for c in nofreq] == [p.cost[c] for c in nofreq]
         if tie:
             rep.tie_fragile_profile += 1
-            if p.policy in (2, 3):
+            if _has_frequent(run, p.policy):
                 fragile_from[i] = -1
         else:
             assert list(cnt[i]) == list(p.cost), (i, cnt[i], p.cost)
@@ -196,12 +199,16 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
                 if i in fragile_from and t >= fragile_from[i]:
                     continue
                 assert np.array_equal(gpos, ora[i]["states"][t]), f"unit {run.units[i]} step {t}: kept set differs"
-                if ora[i]["profile"].policy in (2, 3) and gpos.size:
+                if _has_frequent(run, ora[i]["profile"].policy) and gpos.size:
                     ref = ora[i]["score_states"][t]
                     rel = float(np.max(np.abs(gsc - ref) / np.maximum(np.abs(ref), 1e-6)))
                     rep.max_score_rel_err = max(rep.max_score_rel_err, rel)
                     assert rel < 5e-5, f"unit {run.units[i]} step {t}: score rel err {rel:.2e}"
     return rep
+
+
+def _has_frequent(run: GpuRun, policy: int) -> bool:
+    return policy < 4 and (run.family[policy] & fo.FREQUENT) != 0
 
 
 def _abs_tie(colsum: np.ndarray, k: int) -> bool:

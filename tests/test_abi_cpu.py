@@ -33,7 +33,7 @@ def test_config_struct_matches_header():
     # field order/types of the ctypes mirror against the C declaration
     header = open(os.path.join(ROOT, "include", "fastgen.h")).read()
     body = header[header.index("typedef struct {"):header.index("} fg_config;")]
-    names = re.findall(r"^\s*(?:int32_t|int64_t|double|float)\s+([A-Za-z_]+(?:\s*,\s*[A-Za-z_]+)*)\s*;", body, re.M)
+    names = re.findall(r"^\s*(?:int32_t|int64_t|double|float)\s+([A-Za-z_]+(?:\s*,\s*[A-Za-z_]+)*)(?:\[\d+\])?\s*;", body, re.M)
     flat = [x.strip() for grp in names for x in grp.split(",")]
     assert flat == [f[0] for f in binding.FgConfig._fields_]
 
@@ -50,8 +50,10 @@ def test_workspace_bytes_and_validation(lib):
     nbytes = binding.fastgen_workspace_bytes(good)
     assert nbytes > 8 * 68 * 128 * 2 * 2 and nbytes % 256 == 0
     assert binding.fastgen_workspace_bytes(_cfg(cache_tokens=100)) < nbytes
+    assert binding.fastgen_workspace_bytes(_cfg(family=(8, 4, 12, 0), forced_policy=2)) == nbytes
     for bad in (dict(head_dim=96), dict(num_seqs=3), dict(T=0.0), dict(T=1.5), dict(r_l=-0.1),
-                dict(prompt_len=0), dict(forced_policy=7), dict(num_units=0)):
+                dict(prompt_len=0), dict(forced_policy=7), dict(num_units=0), dict(family=(1, 16, 0, 0)),
+                dict(family=(1, 0, 0, 8), forced_policy=1)):
         assert binding.fastgen_workspace_bytes(_cfg(**bad)) == 0, bad
 
 

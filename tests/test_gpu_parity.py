@@ -191,3 +191,30 @@ def test_no_special_tokens_rows_without_kept_tokens():
     run.cls_u &= 2          # drop the special bit everywhere (both sides read these classes)
     rep = H.compare(run)
     _report("no special tokens, forced policy 0", rep)
+
+
+# Other policy tables: components added in another order or left out (App. A.1, Tables 4-5),
+# single components that are not nested, and the fixed non-adaptive baselines (Sec. 5.1).
+@pytest.mark.parametrize("family", [
+    (8, 8 | 4, 8 | 4 | 1, 15),
+    (1, 1 | 2, 1 | 2 | 8, 15),
+    (1, 1 | 4, 1 | 4 | 8, 0),
+    (2, 4, 8, 1),
+])
+def test_adaptive_choice_over_other_policy_tables(family):
+    w = W["llama7b_b16"].scaled(name="family", layers=2, heads=8, batch=2, prompt_len=640, steps=32, T=0.9,
+                                seed=31)
+    run = H.GpuRun(w, range(w.num_units), family=family)
+    rep = H.compare(run, state_steps=[0, 1, 15, 31])
+    _report(f"family {family}", rep)
+    assert all(c == 4 or family[c] != 0 for c in rep.policies)
+
+
+@pytest.mark.parametrize("mask", [4, 8, 4 | 8, 1 | 8])
+def test_fixed_single_policy_baselines(mask):
+    # every head uses one fixed policy: frequent only, local only, frequent+local, special+local
+    w = W["llama7b_b1"].scaled(name="baseline", layers=1, heads=12, batch=1, prompt_len=500, steps=40, seed=37)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=0, family=(mask, 0, 0, 0))
+    rep = H.compare(run)
+    _report(f"fixed baseline mask {mask}", rep)
+    assert rep.policies == {0: 12}

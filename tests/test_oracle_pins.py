@@ -420,3 +420,105 @@ def test_decode_set_equation_rederived_each_step(policy):
             keep |= {j for j in held if j > p - w}
         score = {j: s for j, s in score.items() if j in keep}
         assert list(res["states"][t]) == sorted(keep)
+
+
+# ------------------------------------- other policy tables (App. A.1 Tables 4-5, Sec. 5.1)
+
+FAMILIES = [
+    (8, 8 | 4, 8 | 4 | 1, 15),   # components added in another order: local first
+    (1, 1 | 2, 1 | 2 | 8, 15),   # local before frequent
+    (1, 1 | 4, 1 | 4 | 8, 0),    # punctuation left out, one id unused
+    (4, 8, 4 | 8, 0),            # the fixed baselines: frequent, local, frequent+local
+    (2, 4, 8, 1),                # single components, not nested
+]
+
+
+def _letters(mask):
+    return "".join(ch for bit, ch in ((1, "s"), (2, "p"), (4, "f"), (8, "l")) if mask & bit)
+
+
+@pytest.mark.parametrize("fam", range(len(FAMILIES)))
+@pytest.mark.parametrize("seed", range(3))
+def test_family_tables_match_brute_force(seed, fam):
+    """Cost and recovery of every member of an arbitrary table, and the literal argmin of
+    Eq. 1 over its usable members, by loops over the dense map."""
+    family = FAMILIES[fam]
+    n, d = 18, 4
+    T = [0.7, 0.85, 0.95][seed]
+    Q, K, _, cls = rand_unit(300 + 7 * seed + fam, n, d, p_punct=0.2, bias=[0.0, 3.0, 6.0][seed])
+    scale, r_l, r_f = 0.5, 0.25, 0.2
+    prof = fo.profile_unit(Q, K, cls, T, r_l, r_f, scale, family=family)
+    A = fo.attention_map(Q, K, scale)
+    w, k = max(1, math.floor(r_l * n)), math.floor(r_f * n)
+    colsum = A.sum(0)
+    ranked = sorted(range(n), key=lambda j: (-colsum[j], j))
+    base = {"s": {j for j in range(n) if cls[j] & 1}, "p": {j for j in range(n) if cls[j] & 2},
+            "f": set(ranked[:k])}
+    cands = [(n, 4)]
+    for c, mask in enumerate(family):
+        if mask == 0:
+            continue
+        combo = _letters(mask)
+        static = set().union(*[base[x] for x in combo if x != "l"]) if combo.strip("l") else set()
+        end_set = static | (set(range(n - w, n)) if "l" in combo else set())
+        rec = 0.0
+        for i in range(n):
+            cols = {j for j in static if j <= i}
+            if "l" in combo:
+                cols |= set(range(max(0, i - w + 1), i + 1))
+            rec += sum(A[i, j] for j in cols)
+        rec /= n
+        assert prof.cost[c] == len(end_set)
+        assert abs(prof.recovery[c] - rec) < 1e-13
+        assert sorted(prof.sets[c]) == sorted(end_set)
+        if rec >= T:
+            cands.append((len(end_set), c))
+    assert prof.policy == min(cands)[1]
+    assert family[prof.policy] != 0 if prof.policy < 4 else True
+
+
+def test_default_family_is_eq2_and_unused_ids_never_chosen():
+    assert fo.DEFAULT_FAMILY == (1, 3, 7, 15)
+    Q, K, _, cls = rand_unit(11, 24, 4, bias=9.0)
+    a = fo.profile_unit(Q, K, cls, 0.5, 0.3, 0.3, 1.0)
+    b = fo.profile_unit(Q, K, cls, 0.5, 0.3, 0.3, 1.0, family=(1, 3, 7, 15))
+    assert a.policy == b.policy and np.array_equal(a.recovery, b.recovery)
+    # T below every recovery: the cheapest usable member wins, never the empty id 0
+    c = fo.profile_unit(Q, K, cls, 1e-9, 0.3, 0.3, 1.0, family=(0, 8, 0, 15))
+    assert c.policy == 1
+
+
+@pytest.mark.parametrize("mask", [4, 8, 4 | 8, 1 | 8, 2 | 4])
+def test_family_decode_set_equation_rederived_each_step(mask):
+    """A forced single-table member: held set, scores and outputs after every step re-derived
+    with python sets (frequent = fixed-ratio heavy hitters, local = sliding window)."""
+    n, d, S = 22, 8, 18
+    scale, r_l, r_f = 0.4, 0.2, 0.3
+    family = (mask, 0, 0, 0)
+    Q, K, V, cls = rand_unit(400 + mask, n, d, p_punct=0.2)
+    q, k, v, cn = _decode_inputs(410 + mask, S, d)
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale, forced_policy=0,
+                      record_states=True, family=family)
+    prof = res["profile"]
+    w = max(1, math.floor(r_l * n))
+    allK, allV, allc = np.vstack([K, k]), np.vstack([V, v]), np.concatenate([cls, cn])
+    score = {int(j): float(prof.colsum[j]) for j in res["init_pos"]}
+    cbits = mask & 3
+    for t in range(S):
+        p = n + t
+        score[p] = 0.0
+        held = sorted(score)
+        lg = np.array([scale * q[t] @ allK[j] for j in held])
+        a = np.exp(lg - lg.max())
+        a /= a.sum()
+        assert np.allclose(res["outs"][t], a @ allV[held], atol=1e-12)
+        keep = {j for j in held if allc[j] & cbits}
+        if mask & 4:
+            for j, aj in zip(held, a):
+                score[j] += aj
+            ranked = sorted(held, key=lambda j: (-score[j], j))
+            keep |= set(ranked[:math.floor(r_f * (p + 1))])
+        if mask & 8:
+            keep |= {j for j in held if j > p - w}
+        score = {j: s for j, s in score.items() if j in keep}
+        assert list(res["states"][t]) == sorted(keep)
