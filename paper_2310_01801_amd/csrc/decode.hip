@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   constexpr int LPR = RB / 16;         // lanes per row
   constexpr int TPL = 64 / LPR;        // rows per wave load
   constexpr int EPL = 16 / ESIZE;      // elements per lane
-  constexpr int ITERS = 64 / TPL;      // loads per wave for its 64 tokens
+  constexpr int TPW = CH / 4;          // tokens per wave
+  constexpr int ITERS = TPW / TPL;     // loads per wave for its tokens
   __shared__ float s_red[8];
   __shared__ float s_o[4][D];
 
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   u32x4 kv[ITERS], vv[ITERS];
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    const int tok = wave * 64 + it * TPL + sub;
+    const int tok = wave * TPW + it * TPL + sub;
     const int slot = start + tok;
     u32x4 kk = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
     if (tok < cnt) {
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
     for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
 #pragma unroll
     for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
-    const int tok = wave * 64 + it * TPL + sub;
+    const int tok = wave * TPW + it * TPL + sub;
     const bool ok = tok < cnt;
     x[it] = ok ? dot * c : FG_NEG_BIG;
     if (ok && g == 0) a.clogit[off + start + tok] = x[it];
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   for (int e = 0; e < EPL; ++e) oacc[e] = 0.f;
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    const int tok = wave * 64 + it * TPL + sub;
+    const int tok = wave * TPW + it * TPL + sub;
     const float p = (tok < cnt) ? fg_exp2(x[it] - M) : 0.f;
     lsum += p;
     float vf[EPL];
