@@ -136,6 +136,21 @@ fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new
                               const void* v_new, const uint8_t* class_new, void* out,
                               void* stream);
 
+/* Stage 2 with the stability probe of Sec. 4 (accumulated attention score of each structure at
+ * later decoding steps): fastgen_decode_step, and in addition
+ *   step_recovery  device [U, 5] double: the mass that this step's attention row (over the
+ *                  tokens held during the step) puts on the tokens of every member of the
+ *                  policy family, evaluated at the current length as in Sec. 3.4 (special /
+ *                  punctuation by class, frequent = the k_f(L) largest cumulative scores
+ *                  including this step's attention, local = the last w positions); entry 4
+ *                  (C_full) is the whole row. For a head on the full cache these are the
+ *                  recoveries of Eq. 1 for the new row.
+ * A probed step keeps the cumulative scores of every unit, not only of the policies that
+ * contain `frequent`; outputs and kept sets are the same as without the probe. */
+fg_status fastgen_decode_step_probe(fastgen_ctx* ctx, const void* q, const void* k_new,
+                                    const void* v_new, const uint8_t* class_new, void* out,
+                                    double* step_recovery, void* stream);
+
 /* Reads back the cache state (test / checkpoint probe; Alg. 1 returns {C, K^, V^}).
  *   lengths    NULL or device [U] int32: tokens held by each unit.
  *   offsets    NULL or device [U + 1] int64: exclusive prefix sum of lengths.

@@ -229,6 +229,8 @@ class Cache:
     cls: np.ndarray             # [len] uint8
     mask: int = 0               # component mask of the policy (ignored for C_full)
     min_gap: float = math.inf   # smallest relative top-k boundary gap seen while decoding
+    probe: Optional[np.ndarray] = None  # step_recovery() of the last probed step
+    probe_gap: float = math.inf         # relative top-k boundary gap of that step
     fragile_step: int = -1      # first decode step whose boundary gap fell below `gap_eps`
 
 
@@ -260,9 +262,33 @@ def kept_after_step(policy: int, mask: int, pos: np.ndarray, cls: np.ndarray, sc
     return keep
 
 
+def step_recovery(c: Cache, a: np.ndarray, p: int, r_l: float, r_f: float, family) -> np.ndarray:
+    """Stability probe (Sec. 4, accumulated attention score at later decoding steps): the mass
+    the new token's attention row `a` puts on each family member's tokens among the tokens held
+    during the step. Members as in Sec. 3.4 at length p + 1: special / punctuation by class,
+    frequent = top k_f(p + 1) cumulative scores (this step's attention included), local =
+    the last w positions. Entry 4 (C_full) is the whole row."""
+    w = local_window(r_l, c.n)
+    top = top_k_positions(c.score, c.pos, frequent_budget(r_f, p + 1))
+    member = {SPECIAL: (c.cls & CLASS_SPECIAL) != 0, PUNCT: (c.cls & CLASS_PUNCT) != 0,
+              FREQUENT: np.isin(c.pos, top), LOCAL: c.pos > p - w}
+    rho = np.zeros(N_POLICIES)
+    for i, mask in enumerate(family):
+        inside = np.zeros(c.pos.size, dtype=bool)
+        for bit in (SPECIAL, PUNCT, FREQUENT, LOCAL):
+            if mask & bit:
+                inside |= member[bit]
+        rho[i] = a[inside].sum()
+    rho[4] = a.sum()
+    return rho
+
+
 def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, cls_new: int,
-                t: int, r_l: float, r_f: float, scale: float, gap_eps: float = 0.0) -> np.ndarray:
-    """One pass of Alg. 2's inner body for one head; returns the attention output o."""
+                t: int, r_l: float, r_f: float, scale: float, gap_eps: float = 0.0,
+                probe_family=None) -> np.ndarray:
+    """One pass of Alg. 2's inner body for one head; returns the attention output o. With
+    `probe_family` the cumulative scores are kept for every policy and c.probe receives
+    step_recovery() of this step."""
     p = c.n + t
     c.K = np.vstack([c.K, np.asarray(k_new, dtype=np.float64)[None, :]])
     c.V = np.vstack([c.V, np.asarray(v_new, dtype=np.float64)[None, :]])
@@ -273,8 +299,13 @@ def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, c
     e = np.exp(s - s.max())
     a = e / e.sum()
     o = a @ c.V
-    if c.policy < 4 and (c.mask & FREQUENT):
-        c.score = c.score + a
+    uses_scores = c.policy < 4 and (c.mask & FREQUENT) != 0
+    if uses_scores or probe_family is not None:
+        c.score = c.score + a   # Sec. 3.4: cumulative attention score of every held token
+    if probe_family is not None:
+        c.probe = step_recovery(c, a, p, r_l, r_f, probe_family)
+        c.probe_gap = boundary_gap(c.score, frequent_budget(r_f, p + 1))
+    if uses_scores:
         g = boundary_gap(c.score, frequent_budget(r_f, p + 1))
         c.min_gap = min(c.min_gap, g)
         if g < gap_eps and c.fragile_step < 0:
@@ -286,8 +317,9 @@ def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, c
 
 def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, scale,
              forced_policy: int = -1, gap_eps: float = 0.0, record_states: bool = False,
-             family=DEFAULT_FAMILY) -> Dict:
-    """Whole path for one head: profile, compact, S decode steps."""
+             family=DEFAULT_FAMILY, probe=False) -> Dict:
+    """Whole path for one head: profile, compact, S decode steps. `probe`: True (every step)
+    or the set of decode steps that run with the stability probe."""
     prof = profile_unit(Q, K, cls, T, r_l, r_f, scale, forced_policy, family)
     cache = compact_unit(K, V, cls, prof, family)
     S = 0 if q_steps is None else len(q_steps)
@@ -297,12 +329,17 @@ def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, sc
     states: List[np.ndarray] = []
     score_states: List[np.ndarray] = []
     init_pos = cache.pos.copy()
+    probed = (lambda t: bool(probe)) if isinstance(probe, bool) else (lambda t: t in probe)
+    probes = np.zeros((S, N_POLICIES))
+    probe_gaps = np.full(S, math.inf)
     for t in range(S):
         outs[t] = decode_step(cache, q_steps[t], k_steps[t], v_steps[t], int(cls_steps[t]),
-                              t, r_l, r_f, scale, gap_eps)
+                              t, r_l, r_f, scale, gap_eps, family if probed(t) else None)
+        if probed(t):
+            probes[t], probe_gaps[t] = cache.probe, cache.probe_gap
         lens[t] = cache.pos.size
         if record_states:
             states.append(cache.pos.copy())
             score_states.append(cache.score.copy())
     return dict(profile=prof, init_pos=init_pos, outs=outs, lens=lens, states=states,
-                score_states=score_states, cache=cache)
+                score_states=score_states, cache=cache, probes=probes, probe_gaps=probe_gaps)

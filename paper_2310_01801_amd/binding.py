@@ -22,7 +22,7 @@ STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_E
 
 EXPORTED = (
     "fastgen_workspace_bytes", "fastgen_create", "fastgen_destroy", "fastgen_profile",
-    "fastgen_compact", "fastgen_decode_step", "fastgen_export_state", "fastgen_last_error",
+    "fastgen_compact", "fastgen_decode_step", "fastgen_decode_step_probe", "fastgen_export_state", "fastgen_last_error",
     "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing",
 )
 PHASES = ("sweep1", "sweep2", "select", "compact", "decode_attn", "decode_update")
@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
     lib.fastgen_compact.argtypes = [vp] * 4
     lib.fastgen_decode_step.restype = ctypes.c_int
     lib.fastgen_decode_step.argtypes = [vp] * 7
+    lib.fastgen_decode_step_probe.restype = ctypes.c_int
+    lib.fastgen_decode_step_probe.argtypes = [vp] * 8
     lib.fastgen_export_state.restype = ctypes.c_int
     lib.fastgen_export_state.argtypes = [vp] * 9
     lib.fastgen_last_error.restype = ctypes.c_char_p
@@ -174,6 +176,16 @@ class FastGen:
         self._check(self.lib.fastgen_decode_step(self._ctx, _ptr(q), _ptr(k_new), _ptr(v_new),
                                                  _ptr(class_new), _ptr(out), _stream()))
         return out
+
+    def fastgen_decode_step_probe(self, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                                  class_new: torch.Tensor, out: Optional[torch.Tensor] = None
+                                  ) -> Tuple[torch.Tensor, torch.Tensor]:
+        if out is None:
+            out = torch.empty((self.cfg.num_units, self.cfg.head_dim), dtype=self.tdtype, device=self.device)
+        rho = torch.empty((self.cfg.num_units, 5), dtype=torch.float64, device=self.device)
+        self._check(self.lib.fastgen_decode_step_probe(self._ctx, _ptr(q), _ptr(k_new), _ptr(v_new),
+                                                       _ptr(class_new), _ptr(out), _ptr(rho), _stream()))
+        return out, rho
 
     def fastgen_export_state(self, rows: bool = False, lengths_only: bool = False) -> Dict[str, torch.Tensor]:
         U, d = self.cfg.num_units, self.cfg.head_dim

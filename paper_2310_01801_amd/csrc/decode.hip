@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   constexpr int RB = D * ESIZE, CPR = RB / 16;
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
+  __shared__ double dred[8];
   const int u = blockIdx.x, tid = threadIdx.x;
   // independent header loads first, then the checks
   const int overflow = a.flags[0];
@@ -187,6 +188,9 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   // policy word: id in the low byte, the policy's component mask (FG_COMP_*) above it
   const int policy = pword & 0xff, comp = pword >> 8;
   const bool freq = (comp & FG_COMP_FREQUENT) != 0;
+  // the stability probe needs the cumulative scores and their top-k for every policy
+  const bool probing = a.probe != nullptr;
+  const bool scored = freq || probing;
   const int64_t off = a.off[u];
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     fg_store_out<ESIZE>(a.out, (size_t)u * D + tid, o * inv);
   }
 
-  if (policy >= 4) {
+  if (policy >= 4 && !probing) {
     if (tid == 0) a.len[u] = L;
     return;
   }
@@ -240,13 +244,13 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         const int cb = cls[j];
         const int pj = pos[j];
         if ((cb & cmask) != 0 || pj > wlo) prot |= 1u << i;
-        if (freq) {
+        if (scored) {
           lg[i] = a.clogit[off + j];
           sc[i] = score[j];
         }
       }
     }
-    if (freq) {
+    if (scored) {
 #pragma unroll
       for (int i = 0; i < NC; ++i) {
         const int j = tid + 256 * i;
@@ -259,13 +263,13 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         }
       }
     }
-    if (freq) {
+    if (scored) {
       const int k_f = fg_budget(a.r_f, p_new + 1);
       __syncthreads();  // score[] is re-read by other threads only if the boundary value is tied
       tk = fg_select_topk_regs<NC>(kc, [&](int j) { return score[j]; },
                                    [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
     }
-  } else if (freq) {
+  } else if (scored) {
     for (int j = tid; j < L; j += 256) {
       const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
       score[j] += (double)aj;
@@ -273,6 +277,33 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     __syncthreads();
     const int k_f = fg_budget(a.r_f, p_new + 1);
     tk = fg_select_topk([&](int j) { return score[j]; }, [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
+  }
+  if (probing) {
+    // Stability probe (Sec. 4): mass of this step's attention row on every family member's
+    // tokens among the held ones (frequent = the top-k just selected, local = last w positions)
+    double r[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int j = tid; j < L; j += 256) {
+      const double aj = (double)(fg_exp2(a.clogit[off + j] - M) * inv);
+      const int c = cls[j];
+      const bool top = fg_in_topk(tk, score[j], (uint32_t)pos[j]), recent = pos[j] > p_new - a.w;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const int m = a.family[p];
+        const bool in = ((m & FG_COMP_SPECIAL) && (c & FG_CLASS_SPECIAL)) || ((m & FG_COMP_PUNCT) && (c & FG_CLASS_PUNCT)) ||
+                        ((m & FG_COMP_FREQUENT) && top) || ((m & FG_COMP_LOCAL) && recent);
+        r[p] += in ? aj : 0.0;
+      }
+      r[4] += aj;
+    }
+#pragma unroll
+    for (int p = 0; p < 5; ++p) {
+      const double t = fg_block_sum_f64(r[p], dred);
+      if (tid == 0) a.probe[(size_t)u * 5 + p] = t;
+    }
+    if (policy >= 4) {
+      if (tid == 0) a.len[u] = L;
+      return;
+    }
   }
   const bool tie_pos = (tk.mode == 2 && tk.pthr != 0xffffffffu);  // rare: boundary value shared
   auto kept = [&](int j) -> bool {  // from memory (large units and the tied case)

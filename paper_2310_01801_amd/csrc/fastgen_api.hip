@@ -46,6 +46,15 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
   return true;
 }
 
+// component masks of policy ids 0..3: the configured table, or the family of Eq. 2
+void family_of(const fg_config& c, int* out) {
+  const bool any = c.family[0] || c.family[1] || c.family[2] || c.family[3];
+  const int eq2[4] = {FG_COMP_SPECIAL, FG_COMP_SPECIAL | FG_COMP_PUNCT,
+                      FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT,
+                      FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT | FG_COMP_LOCAL};
+  for (int i = 0; i < 4; ++i) out[i] = any ? c.family[i] : eq2[i];
+}
+
 fg_layout make_layout(const fg_config& c) {
   fg_layout L;
   memset(&L, 0, sizeof(L));
@@ -227,13 +236,7 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
   sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f;
   sa.forced_policy = c.forced_policy;
-  {
-    const bool any = c.family[0] || c.family[1] || c.family[2] || c.family[3];
-    const int eq2[4] = {FG_COMP_SPECIAL, FG_COMP_SPECIAL | FG_COMP_PUNCT,
-                        FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT,
-                        FG_COMP_SPECIAL | FG_COMP_PUNCT | FG_COMP_FREQUENT | FG_COMP_LOCAL};
-    for (int i = 0; i < 4; ++i) sa.family[i] = any ? c.family[i] : eq2[i];
-  }
+  family_of(c, sa.family);
   {
     PhaseTimer tm(ctx, FG_PHASE_SELECT, s);
     e = fg_launch_select(sa, s);
@@ -278,8 +281,8 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   return FG_OK;
 }
 
-fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new, const void* v_new,
-                              const uint8_t* class_new, void* out, void* stream) {
+static fg_status decode_step_impl(fastgen_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                                  const uint8_t* class_new, void* out, double* probe, void* stream) {
   if (!ctx) return FG_EINVAL;
   if (!q || !k_new || !v_new || !class_new || !out)
     return fail(ctx, FG_EINVAL, "fastgen_decode_step: q, k_new, v_new, class_new and out are required");
@@ -303,6 +306,8 @@ fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new
   da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;
   da.units_per_seq = c.num_units / c.num_seqs; da.w = ctx->w; da.step = ctx->steps_done;
   da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks;
+  da.probe = probe;
+  family_of(c, da.family);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   {
@@ -317,6 +322,19 @@ fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step(update)");
   ctx->steps_done += 1;
   return FG_OK;
+}
+
+fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                              const uint8_t* class_new, void* out, void* stream) {
+  return decode_step_impl(ctx, q, k_new, v_new, class_new, out, nullptr, stream);
+}
+
+fg_status fastgen_decode_step_probe(fastgen_ctx* ctx, const void* q, const void* k_new, const void* v_new,
+                                    const uint8_t* class_new, void* out, double* step_recovery,
+                                    void* stream) {
+  if (!ctx) return FG_EINVAL;
+  if (!step_recovery) return fail(ctx, FG_EINVAL, "fastgen_decode_step_probe: step_recovery is required");
+  return decode_step_impl(ctx, q, k_new, v_new, class_new, out, step_recovery, stream);
 }
 
 fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offsets, int32_t* positions,

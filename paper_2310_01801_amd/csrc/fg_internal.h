@@ -94,6 +94,8 @@ struct fg_decode_args {
   void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; float* clogit;
   const int32_t* chunk_off; const int32_t* item_unit; float* part;
   int U, n, d, dtype, units_per_seq, w, step;
+  int family[4];   // FG_COMP_* mask of policy ids 0..3 (stability probe)
+  double* probe;   // NULL, or [U, 5]: this step's attention mass on every family member
   double r_f;
   float scale;
   int64_t max_chunks;

@@ -32,6 +32,7 @@ GAP_ABS = 1e-30         # scores this small are below float32's exponent range o
 class Report:
     units: int = 0
     margin_excluded: int = 0
+    max_probe_err: float = 0.0
     tie_fragile_profile: int = 0
     tie_fragile_decode: int = 0
     max_recovery_err: float = 0.0
@@ -43,7 +44,8 @@ class Report:
         return (f"units={self.units} policies={dict(sorted(self.policies.items()))} "
                 f"margin_excluded={self.margin_excluded} tie_profile={self.tie_fragile_profile} "
                 f"tie_decode={self.tie_fragile_decode} max|dR|={self.max_recovery_err:.2e} "
-                f"max rel|dscore|={self.max_score_rel_err:.2e} max|do|={self.max_out_err:.2e}")
+                f"max rel|dscore|={self.max_score_rel_err:.2e} max|do|={self.max_out_err:.2e}"
+                + (f" max|dprobe|={self.max_probe_err:.2e}" if self.max_probe_err else ""))
 
 
 def out_tol(w: synth.Workload) -> float:
@@ -85,8 +87,11 @@ class GpuRun:
         torch.cuda.synchronize()
         return pol.cpu().numpy(), rec.cpu().numpy(), cnt.cpu().numpy()
 
-    def step(self, t: int) -> torch.Tensor:
-        return self.fg.fastgen_decode_step(self.q[t], self.k[t], self.v[t], self.cls_dec_u[t])
+    def step(self, t: int, probe: bool = False):
+        args = (self.q[t], self.k[t], self.v[t], self.cls_dec_u[t])
+        if probe:
+            return self.fg.fastgen_decode_step_probe(*args)
+        return self.fg.fastgen_decode_step(*args)
 
     def state(self, rows: bool = False):
         st = self.fg.fastgen_export_state(rows=rows)
@@ -102,7 +107,8 @@ class GpuRun:
         return out
 
 
-def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states: bool = True):
+def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states: bool = True,
+                probe=False):
     """Oracle on unit i of a GpuRun: inputs are the exact values the GPU holds, widened."""
     w = run.w
     S = w.steps if steps is None else steps
@@ -114,11 +120,12 @@ def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states:
     else:
         dec = (None, None, None, None)
     return fo.run_unit(*args, *dec, w.T, w.r_l, w.r_f, scale_of(w), forced_policy=run.forced,
-                       gap_eps=GAP_EPS, record_states=record_states, family=run.family)
+                       gap_eps=GAP_EPS, record_states=record_states, family=run.family, probe=probe)
 
 
 def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Optional[int] = None,
-            state_steps: Optional[Sequence[int]] = None, check_rows: bool = True) -> Report:
+            state_steps: Optional[Sequence[int]] = None, check_rows: bool = True,
+            probe_steps: Sequence[int] = ()) -> Report:
     """Runs both sides and asserts parity. `check_units` are indices into run.units (default
     all); `state_steps` are the decode steps after which kept sets and scores are compared
     (default: every step)."""
@@ -128,7 +135,8 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
     rep = Report(units=len(idx))
     tol = out_tol(w)
 
-    ora = {i: oracle_unit(run, i, S) for i in idx}
+    probe_steps = set(probe_steps)
+    ora = {i: oracle_unit(run, i, S, probe=probe_steps) for i in idx}
     pol, rec, cnt = run.profile_and_compact()
 
     excluded = set()     # margin-excluded: nothing discrete is compared
@@ -180,7 +188,13 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
     # decode
     state_steps = set(range(S)) if state_steps is None else set(state_steps)
     for t in range(S):
-        out = run.step(t).float().cpu().numpy()
+        rho = None
+        if t in probe_steps:
+            out, rho = run.step(t, probe=True)
+            rho = rho.cpu().numpy()
+        else:
+            out = run.step(t)
+        out = out.float().cpu().numpy()
         st = run.state() if t in state_steps else None
         for i in idx:
             o_ref = ora[i]["outs"][t]
@@ -193,6 +207,13 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
             err = float(np.max(np.abs(out[i] - o_ref)))
             rep.max_out_err = max(rep.max_out_err, err)
             assert err <= tol, f"unit {run.units[i]} step {t}: |o - oracle| = {err:.3e} > {tol}"
+            if rho is not None:
+                # members that contain `frequent` depend on the top-k boundary: skipped at a near-tie
+                tie = ora[i]["probe_gaps"][t] < GAP_EPS or (i in fragile_from and t >= fragile_from[i])
+                members = [c for c in range(5) if not (tie and c < 4 and run.family[c] & fo.FREQUENT)]
+                perr = float(np.max(np.abs(rho[i][members] - ora[i]["probes"][t][members])))
+                rep.max_probe_err = max(rep.max_probe_err, perr)
+                assert perr < 2e-5, f"unit {run.units[i]} step {t}: step recovery {rho[i]} vs {ora[i]['probes'][t]}"
             if st is not None:
                 gpos, gsc = st[i]
                 assert gpos.size == ora[i]["lens"][t], f"unit {run.units[i]} step {t}: length {gpos.size} vs {ora[i]['lens'][t]}"

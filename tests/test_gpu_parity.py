@@ -136,7 +136,7 @@ def test_llama7b_full_size_sampled_units():
     run = H.GpuRun(w, range(w.num_units))
     rng = np.random.default_rng(5)
     sample = sorted(rng.choice(w.num_units, size=12, replace=False).tolist())
-    rep = H.compare(run, check_units=sample, state_steps=[0, 11, 23], check_rows=False)
+    rep = H.compare(run, check_units=sample, state_steps=[0, 11, 23], check_rows=False, probe_steps=[10, 20])
     _report("llama7b_b1 full size, 12 sampled units", rep)
 
 
@@ -144,12 +144,13 @@ def test_llama7b_full_size_sampled_units():
 # The decode horizon is shortened (the step logic is covered above; these runs are about the
 # shapes, the ragged-length mix and the grid sizes of the large launches).
 
-def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0):
+def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0, probe_steps=()):
     w = W[name].scaled(steps=steps) if T is None else W[name].scaled(steps=steps, T=T)
     run = H.GpuRun(w, range(w.num_units))
     rng = np.random.default_rng(seed)
     sample = sorted(rng.choice(w.num_units, size=n_sample, replace=False).tolist())
-    rep = H.compare(run, check_units=sample, state_steps=state_steps or [0, steps - 1], check_rows=False)
+    rep = H.compare(run, check_units=sample, state_steps=state_steps or [0, steps - 1], check_rows=False,
+                    probe_steps=probe_steps)
     _report(f"{name} full size (T={w.T}), {n_sample} sampled units, {steps} steps", rep)
     return rep
 
@@ -164,7 +165,8 @@ def test_llama13b_b4_full_size_sampled_units():
 
 
 def test_llama65b_b2_full_size_sampled_units():
-    _full_size("llama65b_b2", 4, 6, seed=65)
+    # two probed steps: units above 6144 held tokens take the update kernel's large-unit path
+    _full_size("llama65b_b2", 4, 6, seed=65, probe_steps=[1, 4])
 
 
 @pytest.mark.parametrize("kw", [
@@ -218,3 +220,26 @@ def test_fixed_single_policy_baselines(mask):
     rep = H.compare(run)
     _report(f"fixed baseline mask {mask}", rep)
     assert rep.policies == {0: 12}
+
+
+# Stability probe (Sec. 4): per decode step, the attention mass on every family member.
+@pytest.mark.parametrize("forced", [4, -1, 1])
+def test_decode_step_probe(forced):
+    # forced 4: every head on the full cache, probed at every step -> the row recoveries of Eq. 1;
+    # adaptive / class-only: probing only some steps must leave outputs and kept sets as they are
+    w = W["llama7b_b1"].scaled(name="probe", layers=1, heads=12, batch=2, prompt_len=400, steps=32, seed=41)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=forced)
+    steps = range(32) if forced == 4 else [0, 9, 10, 19, 31]
+    rep = H.compare(run, probe_steps=steps, state_steps=[0, 9, 10, 11, 31])
+    _report(f"probe forced={forced}", rep)
+    assert rep.max_probe_err > 0.0
+
+
+def test_decode_step_probe_needs_output_buffer():
+    w = W["tiny"]
+    run = H.GpuRun(w, range(w.num_units))
+    run.profile_and_compact()
+    fg = run.fg
+    st = fg.lib.fastgen_decode_step_probe(fg._ctx, run.q[0].data_ptr(), run.k[0].data_ptr(), run.v[0].data_ptr(),
+                                          run.cls_dec_u[0].data_ptr(), run.q[0].data_ptr(), None, None)
+    assert st == 1  # FG_EINVAL, nothing launched

@@ -522,3 +522,49 @@ def test_family_decode_set_equation_rederived_each_step(mask):
             keep |= {j for j in held if j > p - w}
         score = {j: s for j, s in score.items() if j in keep}
         assert list(res["states"][t]) == sorted(keep)
+
+
+# ----------------------------------------- stability probe at decode steps (Sec. 4, Fig. 4)
+
+@pytest.mark.parametrize("policy", [4, 3, 1])
+def test_step_recovery_rederived_with_sets(policy):
+    """Per decode step: mass of the new token's attention row on special / +punct / +frequent /
+    +local tokens among the held ones, from python dicts. With the full cache (policy 4) this is
+    the row's recovery under every member of Eq. 2's family; the members are nested, the last
+    entry is the whole row."""
+    n, d, S = 24, 8, 16
+    scale, r_l, r_f = 0.4, 0.2, 0.3
+    Q, K, V, cls = rand_unit(500 + policy, n, d, p_punct=0.2)
+    q, k, v, cn = _decode_inputs(510 + policy, S, d)
+    res = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale, forced_policy=policy,
+                      record_states=True, probe=True)
+    prof = res["profile"]
+    w = max(1, math.floor(r_l * n))
+    allK, allc = np.vstack([K, k]), np.concatenate([cls, cn])
+    score = {int(j): float(prof.colsum[j]) for j in res["init_pos"]}
+    for t in range(S):
+        p = n + t
+        score[p] = 0.0
+        held = sorted(score)
+        lg = np.array([scale * q[t] @ allK[j] for j in held])
+        a = np.exp(lg - lg.max())
+        a /= a.sum()
+        att = dict(zip(held, a))
+        for j in held:
+            score[j] += att[j]      # probing keeps the cumulative score for every policy
+        ranked = sorted(held, key=lambda j: (-score[j], j))
+        sets = [{j for j in held if allc[j] & 1}]
+        sets.append(sets[0] | {j for j in held if allc[j] & 2})
+        sets.append(sets[1] | set(ranked[:math.floor(r_f * (p + 1))]))
+        sets.append(sets[2] | {j for j in held if j > p - w})
+        rho = res["probes"][t]
+        for c in range(4):
+            assert abs(rho[c] - sum(att[j] for j in sets[c])) < 1e-13
+        assert abs(rho[4] - 1.0) < 1e-13 and np.all(np.diff(rho) >= -1e-15)
+        keep = set(res["states"][t])
+        score = {j: s for j, s in score.items() if j in keep}
+    # probing does not change what is kept or computed
+    ref = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale, forced_policy=policy,
+                      record_states=True)
+    assert np.array_equal(ref["outs"], res["outs"])
+    assert all(np.array_equal(x, y) for x, y in zip(ref["states"], res["states"]))
