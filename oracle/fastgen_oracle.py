@@ -33,6 +33,12 @@ Readings taken where the paper is silent (each is a *reading*, stated once here)
       starts at 0 and receives this step's attention like every other held token; scores
       are only maintained for policies that contain `frequent`.
   R8  R >= T (non-strict), as Eq. 1's "<=".
+  R13 grouped-query attention (named future work in Sec. 5.1 and the Conclusion, no rule
+      given): G query heads share one K/V head and therefore one cache and one policy. The
+      extension taken here reduces to the paper at G = 1: Eq. 1 averages over the rows of
+      all G heads (recovery = mean kept mass over the G*n rows), a token's cumulative
+      attention score is the sum over the G heads, every head attends over the shared
+      compressed cache while decoding, and a step adds the G attention rows to the scores.
 
 Pinned by tests/test_oracle_pins.py (closed forms for Q = 0, brute force over subsets,
 textbook softmax/attention, TV-distance identity, nestedness, full-cache invariants).
@@ -183,10 +189,13 @@ def select_policy(cost: np.ndarray, recovery: np.ndarray, T: float, usable=None)
 
 def profile_unit(Q: np.ndarray, K: np.ndarray, cls: np.ndarray, T: float, r_l: float,
                  r_f: float, scale: float, forced_policy: int = -1, family=DEFAULT_FAMILY) -> Profile:
-    """Alg. 1 up to the choice of C for one head."""
-    A = attention_map(Q, K, scale)
-    n = A.shape[0]
-    colsum = A.sum(axis=0)
+    """Alg. 1 up to the choice of C for one K/V head. Q is [n, d], or [G, n, d] for the G
+    query heads that share it (R13)."""
+    Qg = np.asarray(Q, dtype=np.float64)
+    Qg = Qg[None] if Qg.ndim == 2 else Qg          # [G, n, d]: the query heads sharing this K/V head
+    maps = [attention_map(Qh, K, scale) for Qh in Qg]
+    n = maps[0].shape[0]
+    colsum = np.sum([A.sum(axis=0) for A in maps], axis=0)
     cls = np.asarray(cls)
     sets = kept_sets(cls, colsum, r_l, r_f, family)
     comp = component_sets(cls, colsum, r_l, r_f)
@@ -197,13 +206,13 @@ def profile_unit(Q: np.ndarray, K: np.ndarray, cls: np.ndarray, T: float, r_l: f
         static = np.zeros(n, dtype=bool)
         if c == 4:
             static[:] = True
-            rec[c] = recovery_dense(A, static, 0)
-            continue
-        # the local component is row-relative on the prompt; the others are static column sets
-        for bit in (SPECIAL, PUNCT, FREQUENT):
-            if family[c] & bit:
-                static[comp[bit]] = True
-        rec[c] = recovery_dense(A, static, w if family[c] & LOCAL else 0)
+        else:
+            # the local component is row-relative on the prompt; the others are static column sets
+            for bit in (SPECIAL, PUNCT, FREQUENT):
+                if family[c] & bit:
+                    static[comp[bit]] = True
+        window = w if (c < 4 and family[c] & LOCAL) else 0
+        rec[c] = float(np.mean([recovery_dense(A, static, window) for A in maps]))
     cost = np.array([s.size for s in sets], dtype=np.int64)
     policy = select_policy(cost, rec, T, usable) if forced_policy < 0 else int(forced_policy)
     margins = [abs(rec[c] - T) for c in range(4) if usable[c]]
@@ -264,7 +273,7 @@ def kept_after_step(policy: int, mask: int, pos: np.ndarray, cls: np.ndarray, sc
 
 def step_recovery(c: Cache, a: np.ndarray, p: int, r_l: float, r_f: float, family) -> np.ndarray:
     """Stability probe (Sec. 4, accumulated attention score at later decoding steps): the mass
-    the new token's attention row `a` puts on each family member's tokens among the tokens held
+    the new token's attention row `a` (the mean of the G rows for grouped heads) puts on each family member's tokens among the tokens held
     during the step. Members as in Sec. 3.4 at length p + 1: special / punctuation by class,
     frequent = top k_f(p + 1) cumulative scores (this step's attention included), local =
     the last w positions. Entry 4 (C_full) is the whole row."""
@@ -286,7 +295,8 @@ def step_recovery(c: Cache, a: np.ndarray, p: int, r_l: float, r_f: float, famil
 def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, cls_new: int,
                 t: int, r_l: float, r_f: float, scale: float, gap_eps: float = 0.0,
                 probe_family=None) -> np.ndarray:
-    """One pass of Alg. 2's inner body for one head; returns the attention output o. With
+    """One pass of Alg. 2's inner body for one K/V head; q is [d], or [G, d] for the query
+    heads sharing it; returns the attention output o ([d] or [G, d]). With
     `probe_family` the cumulative scores are kept for every policy and c.probe receives
     step_recovery() of this step."""
     p = c.n + t
@@ -295,15 +305,20 @@ def decode_step(c: Cache, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, c
     c.score = np.append(c.score, 0.0)
     c.pos = np.append(c.pos, p)
     c.cls = np.append(c.cls, np.uint8(cls_new))
-    s = (c.K @ np.asarray(q, dtype=np.float64)) * float(scale)
-    e = np.exp(s - s.max())
-    a = e / e.sum()
-    o = a @ c.V
+    qg = np.asarray(q, dtype=np.float64)
+    single = qg.ndim == 1
+    qg = qg[None] if single else qg                # [G, d]
+    s = (qg @ c.K.T) * float(scale)                # [G, len]
+    e = np.exp(s - s.max(axis=1, keepdims=True))
+    ag = e / e.sum(axis=1, keepdims=True)          # one attention row per query head
+    o = ag @ c.V
+    o = o[0] if single else o
+    a = ag.sum(axis=0)                             # what the step adds to the cumulative scores
     uses_scores = c.policy < 4 and (c.mask & FREQUENT) != 0
     if uses_scores or probe_family is not None:
         c.score = c.score + a   # Sec. 3.4: cumulative attention score of every held token
     if probe_family is not None:
-        c.probe = step_recovery(c, a, p, r_l, r_f, probe_family)
+        c.probe = step_recovery(c, a / ag.shape[0], p, r_l, r_f, probe_family)
         c.probe_gap = boundary_gap(c.score, frequent_budget(r_f, p + 1))
     if uses_scores:
         g = boundary_gap(c.score, frequent_budget(r_f, p + 1))
@@ -324,7 +339,7 @@ def run_unit(Q, K, V, cls, q_steps, k_steps, v_steps, cls_steps, T, r_l, r_f, sc
     cache = compact_unit(K, V, cls, prof, family)
     S = 0 if q_steps is None else len(q_steps)
     d = np.asarray(K).shape[1]
-    outs = np.zeros((S, d))
+    outs = np.zeros((S, d)) if S == 0 or np.asarray(q_steps[0]).ndim == 1 else np.zeros((S, len(q_steps[0]), d))
     lens = np.zeros(S, dtype=np.int64)
     states: List[np.ndarray] = []
     score_states: List[np.ndarray] = []

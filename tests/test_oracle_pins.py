@@ -568,3 +568,77 @@ def test_step_recovery_rederived_with_sets(policy):
                       record_states=True)
     assert np.array_equal(ref["outs"], res["outs"])
     assert all(np.array_equal(x, y) for x, y in zip(ref["states"], res["states"]))
+
+
+# ------------------------------------ grouped query heads sharing one K/V head (reading R13)
+
+def test_group_of_identical_heads_equals_one_head():
+    """G copies of one query head: same recoveries, policy and kept sets, G-fold scores, and
+    every head's decode output equals the single-head output."""
+    n, d, S, G = 28, 8, 14, 3
+    scale, r_l, r_f = 0.4, 0.2, 0.3
+    Q, K, V, cls = rand_unit(600, n, d, p_punct=0.2, bias=2.0)
+    q, k, v, cn = _decode_inputs(601, S, d)
+    for policy in (-1, 2, 3):
+        one = fo.run_unit(Q, K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale, forced_policy=policy,
+                          record_states=True)
+        grp = fo.run_unit(np.stack([Q] * G), K, V, cls, np.stack([q] * G, axis=1), k, v, cn, 0.9, r_l, r_f,
+                          scale, forced_policy=policy, record_states=True)
+        assert grp["profile"].policy == one["profile"].policy
+        assert np.allclose(grp["profile"].recovery, one["profile"].recovery, atol=1e-14)
+        assert np.allclose(grp["profile"].colsum, G * one["profile"].colsum, rtol=1e-14)
+        for t in range(S):
+            assert np.array_equal(grp["states"][t], one["states"][t])
+            for g in range(G):
+                assert np.allclose(grp["outs"][t][g], one["outs"][t], atol=1e-13)
+            assert np.allclose(grp["score_states"][t], G * one["score_states"][t], rtol=1e-12)
+
+
+@pytest.mark.parametrize("policy", [2, 3])
+def test_group_of_two_heads_rederived_by_loops(policy):
+    """G = 2 different query heads: recoveries as the mean over the 2n rows, scores as the sum of
+    both heads' attention, one shared kept set -- by loops and python sets."""
+    n, d, S, G = 20, 6, 12, 2
+    scale, r_l, r_f = 0.5, 0.25, 0.3
+    Q0, K, V, cls = rand_unit(610 + policy, n, d, p_punct=0.2, bias=1.5)
+    Q1 = np.random.default_rng(620 + policy).standard_normal((n, d))
+    rng = np.random.default_rng(630 + policy)
+    q = rng.standard_normal((S, G, d))
+    _, k, v, cn = _decode_inputs(640 + policy, S, d)
+    res = fo.run_unit(np.stack([Q0, Q1]), K, V, cls, q, k, v, cn, 0.9, r_l, r_f, scale,
+                      forced_policy=policy, record_states=True)
+    prof = res["profile"]
+    A = [fo.attention_map(Q0, K, scale), fo.attention_map(Q1, K, scale)]
+    w, kf = max(1, math.floor(r_l * n)), math.floor(r_f * n)
+    colsum = [sum(A[g][i, j] for g in range(G) for i in range(n)) for j in range(n)]
+    assert np.allclose(prof.colsum, colsum, atol=1e-13)
+    ranked = sorted(range(n), key=lambda j: (-colsum[j], j))
+    static = {j for j in range(n) if cls[j] & 3} | set(ranked[:kf])
+    rec2 = sum(A[g][i, j] for g in range(G) for i in range(n) for j in static if j <= i) / (G * n)
+    assert abs(prof.recovery[2] - rec2) < 1e-13
+    rec3 = 0.0
+    for g in range(G):
+        for i in range(n):
+            cols = {j for j in static if j <= i} | set(range(max(0, i - w + 1), i + 1))
+            rec3 += sum(A[g][i, j] for j in cols)
+    assert abs(prof.recovery[3] - rec3 / (G * n)) < 1e-13
+    # decode: one kept set, G outputs, scores += both rows
+    allK, allV, allc = np.vstack([K, k]), np.vstack([V, v]), np.concatenate([cls, cn])
+    score = {int(j): float(colsum[j]) for j in res["init_pos"]}
+    for t in range(S):
+        p = n + t
+        score[p] = 0.0
+        held = sorted(score)
+        for g in range(G):
+            lg = np.array([scale * q[t, g] @ allK[j] for j in held])
+            a = np.exp(lg - lg.max())
+            a /= a.sum()
+            assert np.allclose(res["outs"][t][g], a @ allV[held], atol=1e-12)
+            for j, aj in zip(held, a):
+                score[j] += aj
+        rk = sorted(held, key=lambda j: (-score[j], j))
+        keep = set(rk[:math.floor(r_f * (p + 1))]) | {j for j in held if allc[j] & 3}
+        if policy == 3:
+            keep |= {j for j in held if j > p - w}
+        score = {j: s for j, s in score.items() if j in keep}
+        assert list(res["states"][t]) == sorted(keep)
