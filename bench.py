@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cache-tokens", type=int, default=0, help="cache pool capacity in tokens (0 = worst case)")
+    ap.add_argument("--group-size", type=int, default=1,
+                    help="query heads per K/V head (grouped-query variant of the workload; not a BASELINE config)")
     ap.add_argument("--forced-policy", type=int, default=-1, help="every unit uses this policy (non-adaptive baselines)")
     ap.add_argument("--cpu-sample-units", type=int, default=0, help="0 = sized for ~20 s")
     return ap.parse_args()
@@ -87,13 +89,18 @@ def main():
     units = list(range(U))
     Q, K, V = synth.prompt_batch(w, plan, cls_p, units, dev)
     q, k, v = synth.decode_batch(w, plan, cls_d, units, dev) if S > 0 else (None, None, None)
+    G = max(1, args.group_size)
+    if G > 1:
+        Q = torch.cat([synth.prompt_group_queries(w, plan, cls_p, u, G, dev) for u in units])
+        if S > 0:
+            q = torch.cat([synth.decode_group_queries(w, plan, cls_d, u, G, dev) for u in units], dim=1).contiguous()
     cls_p_d = torch.from_numpy(cls_p).to(dev)
     cls_d_d = torch.from_numpy(cls_d).to(dev)
-    out = torch.empty((U, d), dtype=w.torch_dtype, device=dev)
+    out = torch.empty((U * max(1, args.group_size), d), dtype=w.torch_dtype, device=dev)
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
-    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f, 0.0, args.forced_policy, args.cache_tokens)
+    cfg = binding.make_config(U, B, d, w.torch_dtype, n, S, w.T, w.r_l, w.r_f, 0.0, args.forced_policy, args.cache_tokens, None, max(1, args.group_size))
     workspace = torch.empty(binding.fastgen_workspace_bytes(cfg), dtype=torch.uint8, device=dev)
 
     def one_pass(timing=False):
@@ -139,7 +146,7 @@ def main():
     launches = {name: runs[0]["timing"][name][1] for name in binding.PHASES}
 
     # ---- roofline of the profiling sweeps (matrix-core bound)
-    flop_sweep = float(d) * n * (n + 1) * U            # causal QK^T, one sweep
+    flop_sweep = float(d) * n * (n + 1) * U * max(1, args.group_size)   # causal QK^T, one sweep
     sweeps_ms = phase["sweep1"] + phase["sweep2"]
     mfma_achieved = 2 * flop_sweep / (sweeps_ms * 1e-3)
     roof_profile = dict(kernel="fg_profile_mfma_kernel (both sweeps)", bound="mfma",
@@ -195,7 +202,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.layers} layers x {w.heads} heads, batch {B}, head_dim {d}, "
                                f"{w.dtype}, prompt {n}, {S} decode steps, T={w.T}, r_l={w.r_l}, r_f={w.r_f} "
                                f"(BASELINE configs[1] when llama7b_b1)",
-                   "units": U, "policy_histogram": pol_hist, "input_generation_s": gen_s},
+                   "units": U, "query_heads_per_unit": max(1, args.group_size),
+                   "policy_histogram": pol_hist, "input_generation_s": gen_s},
         "decode_attn_steps_per_s": decode_steps_per_s,
         "stage1_ms": s1, "stage2_ms": s2,
         "phase_ms": phase, "phase_launches": launches,

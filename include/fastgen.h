@@ -89,6 +89,12 @@ typedef struct {
   int32_t family[4];      /* FG_COMP_* mask of policy ids 0..3; all zero selects Eq. 2's
                              family; otherwise a zero entry is an unused id. Eq. 1 takes the
                              cheapest usable policy reaching T (equal cost: smaller id)       */
+  int32_t group_size;     /* G: query heads that share one K/V head (grouped-query attention;
+                             0 or 1 = multi-head attention as in the paper, at most 16). The
+                             cache and the policy belong to the K/V head. Arrays of queries
+                             and outputs (Q, lse_opt, q, out) then have U * G units, query
+                             head g of unit u at index u * G + g; Eq. 1 averages over the rows
+                             of all G heads and the cumulative scores add their attention     */
 } fg_config;
 
 /* Size in bytes of the device workspace a context with this configuration needs
@@ -104,9 +110,10 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
 fg_status fastgen_destroy(fastgen_ctx* ctx);
 
 /* Stage 1a -- attention profiling and policy choice (Alg. 1, Sec. 3.3 Eq. 1, Sec. 3.4 Eq. 2).
- *   Q, K         device [U, n, d] in cfg.dtype, 16-byte aligned: the prompt's queries/keys.
+ *   Q, K         device [U (Q: U * G), n, d] in cfg.dtype, 16-byte aligned: the prompt's
+ *                queries/keys.
  *   token_class  device [B, n] uint8, FG_CLASS_* bits of every prompt token.
- *   lse_opt      NULL, or device [U, n] float: natural-log row log-sum-exp of the causal,
+ *   lse_opt      NULL, or device [U * G, n] float: natural-log row log-sum-exp of the causal,
  *                scaled logits as a prefill attention kernel produces it; when given, the
  *                pass that computes it is skipped.
  *   policy       NULL or device [U] int32: chosen policy id of every unit.
@@ -125,9 +132,10 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K,
 fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* stream);
 
 /* Stage 2 -- one decode step for every unit (Alg. 2 inner loop; policies of Sec. 3.4).
- *   q, k_new, v_new  device [U, d] in cfg.dtype: the new token's query/key/value per unit.
+ *   q, k_new, v_new  device [U, d] (q: [U * G, d]) in cfg.dtype: the new token's
+ *                    query/key/value per unit.
  *   class_new        device [B] uint8: FG_CLASS_* bits of the new token of each sequence.
- *   out              device [U, d] in cfg.dtype: softmax(scale * q K^T) V over the held
+ *   out              device [U * G, d] in cfg.dtype: softmax(scale * q K^T) V over the held
  *                    tokens including the new one.
  * After the output is formed the cumulative scores are updated (policies containing
  * `frequent`) and every unit's kept set is re-derived from its policy; evicted tokens are

@@ -34,7 +34,7 @@ class FgConfig(ctypes.Structure):
         ("dtype", ctypes.c_int32), ("prompt_len", ctypes.c_int32), ("max_new_tokens", ctypes.c_int32),
         ("T", ctypes.c_double), ("r_l", ctypes.c_double), ("r_f", ctypes.c_double),
         ("softmax_scale", ctypes.c_float), ("forced_policy", ctypes.c_int32),
-        ("cache_tokens", ctypes.c_int64), ("family", ctypes.c_int32 * 4),
+        ("cache_tokens", ctypes.c_int64), ("family", ctypes.c_int32 * 4), ("group_size", ctypes.c_int32),
     ]
 
 
@@ -96,12 +96,13 @@ def _stream() -> int:
 
 def make_config(num_units: int, num_seqs: int, head_dim: int, dtype: torch.dtype, prompt_len: int,
                 max_new_tokens: int, T: float, r_l: float, r_f: float, softmax_scale: float = 0.0,
-                forced_policy: int = -1, cache_tokens: int = 0, family=None) -> FgConfig:
+                forced_policy: int = -1, cache_tokens: int = 0, family=None,
+                group_size: int = 1) -> FgConfig:
     """family: None (the family of Eq. 2) or four FG_COMP_* masks for policy ids 0..3."""
     code = {torch.float32: FG_F32, torch.bfloat16: FG_BF16}[dtype]
     fam = (ctypes.c_int32 * 4)(*(family if family is not None else (0, 0, 0, 0)))
     return FgConfig(num_units, num_seqs, head_dim, code, prompt_len, max_new_tokens, T, r_l, r_f,
-                    softmax_scale, forced_policy, cache_tokens, fam)
+                    softmax_scale, forced_policy, cache_tokens, fam, group_size)
 
 
 def fastgen_workspace_bytes(cfg: FgConfig) -> int:
@@ -172,7 +173,8 @@ class FastGen:
     def fastgen_decode_step(self, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
                             class_new: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
         if out is None:
-            out = torch.empty((self.cfg.num_units, self.cfg.head_dim), dtype=self.tdtype, device=self.device)
+            out = torch.empty((self.cfg.num_units * max(1, self.cfg.group_size), self.cfg.head_dim),
+                              dtype=self.tdtype, device=self.device)
         self._check(self.lib.fastgen_decode_step(self._ctx, _ptr(q), _ptr(k_new), _ptr(v_new),
                                                  _ptr(class_new), _ptr(out), _stream()))
         return out
@@ -181,7 +183,8 @@ class FastGen:
                                   class_new: torch.Tensor, out: Optional[torch.Tensor] = None
                                   ) -> Tuple[torch.Tensor, torch.Tensor]:
         if out is None:
-            out = torch.empty((self.cfg.num_units, self.cfg.head_dim), dtype=self.tdtype, device=self.device)
+            out = torch.empty((self.cfg.num_units * max(1, self.cfg.group_size), self.cfg.head_dim),
+                              dtype=self.tdtype, device=self.device)
         rho = torch.empty((self.cfg.num_units, 5), dtype=torch.float64, device=self.device)
         self._check(self.lib.fastgen_decode_step_probe(self._ctx, _ptr(q), _ptr(k_new), _ptr(v_new),
                                                        _ptr(class_new), _ptr(out), _ptr(rho), _stream()))

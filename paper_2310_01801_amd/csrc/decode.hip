@@ -36,7 +36,9 @@ __device__ __forceinline__ void fg_unpack<4>(const u32x4& v, float* f) {
   for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(v[i]);
 }
 
-template <int ESIZE, int D>
+// GRP: several query heads per unit (a.G > 1); without it G is the constant 1 and the code is
+// the plain multi-head path.
+template <int ESIZE, int D, bool GRP>
 __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a) {
   constexpr int RB = D * ESIZE;        // bytes per row
   constexpr int LPR = RB / 16;         // lanes per row
@@ -73,10 +75,19 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   const char* kn = static_cast<const char*>(a.k_new) + (size_t)u * RB;
   const char* vn = static_cast<const char*>(a.v_new) + (size_t)u * RB;
 
+  // G query heads share the unit's cache: its rows are loaded once and used by every head
+  const int G = GRP ? a.G : 1;
+  const char* qu = static_cast<const char*>(a.q) + (size_t)u * G * RB;
   float qv[EPL];
   {
-    const u32x4 t = *reinterpret_cast<const u32x4*>(static_cast<const char*>(a.q) + (size_t)u * RB + g * 16);
+    const u32x4 t = *reinterpret_cast<const u32x4*>(qu + g * 16);
     fg_unpack<ESIZE>(t, qv);
+  }
+  // grouped heads: all G query vectors are staged in LDS while the cache rows are in flight
+  __shared__ __attribute__((aligned(16))) unsigned char s_q[GRP ? 16 * RB : 16];
+  if (GRP) {
+    for (int i = tid; i < G * LPR; i += 256)
+      *reinterpret_cast<u32x4*>(&s_q[i * 16]) = *reinterpret_cast<const u32x4*>(qu + (size_t)i * 16);
   }
 
   u32x4 kv[ITERS], vv[ITERS];
@@ -105,6 +116,20 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
     vv[it] = vw;
   }
 
+  for (int h = 0; h < G; ++h) {
+  if (GRP) {
+    if (h == 0) __syncthreads();
+    const u32x4 t = *reinterpret_cast<const u32x4*>(&s_q[h * RB + g * 16]);
+    fg_unpack<ESIZE>(t, qv);
+  }
+  if (GRP) {
+    // keep the cache rows packed across the head loop (unpacking them once for all heads would
+    // need twice the register file)
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      asm volatile("" : "+v"(kv[it]), "+v"(vv[it]));
+    }
+  }
   // scaled logits (log2 domain): x = c * q.k, one value per token shared by its LPR lanes
   float x[ITERS];
   float mx = FG_NEG_BIG;
@@ -120,7 +145,7 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
     const int tok = wave * TPW + it * TPL + sub;
     const bool ok = tok < cnt;
     x[it] = ok ? dot * c : FG_NEG_BIG;
-    if (ok && g == 0) a.clogit[off + start + tok] = x[it];
+    if (ok && g == 0) a.clogit[(off + start + tok) * G + h] = x[it];
     mx = fmaxf(mx, x[it]);
   }
 #pragma unroll
@@ -156,11 +181,13 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   }
   if (lane == 0) s_red[4 + wave] = lsum;
   __syncthreads();
-  float* part = a.part + (size_t)item * (D + 2);
+  float* part = a.part + ((size_t)item * G + h) * (D + 2);
   if (tid < D) part[2 + tid] = (s_o[0][tid] + s_o[1][tid]) + (s_o[2][tid] + s_o[3][tid]);
   if (tid == 0) {
     part[0] = M;
     part[1] = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+  }
+  if (h + 1 < G) __syncthreads();  // the reduction scratch is reused by the next head
   }
 }
 
@@ -175,13 +202,15 @@ __device__ __forceinline__ void fg_store_out<4>(void* out, size_t idx, float v) 
   static_cast<float*>(out)[idx] = v;
 }
 
-template <int ESIZE, int D>
+template <int ESIZE, int D, bool GRP>
 __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a) {
   constexpr int RB = D * ESIZE, CPR = RB / 16;
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
   __shared__ double dred[8];
+  __shared__ float s_M[16], s_inv[16];  // per query head: merged max and 1 / sum
   const int u = blockIdx.x, tid = threadIdx.x;
+  const int G = GRP ? a.G : 1;
   // independent header loads first, then the checks
   const int overflow = a.flags[0];
   const int Lold = a.len[u], cap = a.cap[u], c_off = a.chunk_off[u], pword = a.policy[u];
@@ -195,20 +224,40 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
   const int nch = (L + CH - 1) / CH;
-  const float* part = a.part + (size_t)c_off * (D + 2);
+  const float* part = a.part + (size_t)c_off * G * (D + 2);
 
-  // ---- merge the chunk partials: o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M)
-  float M = FG_NEG_BIG;
-  for (int cix = 0; cix < nch; ++cix) M = fmaxf(M, part[(size_t)cix * (D + 2)]);
-  float Lsum = 0.f;
-  for (int cix = 0; cix < nch; ++cix)
-    Lsum += part[(size_t)cix * (D + 2) + 1] * fg_exp2(part[(size_t)cix * (D + 2)] - M);
-  const float inv = 1.0f / Lsum;
-  if (tid < D) {
-    float o = 0.f;
-    for (int cix = 0; cix < nch; ++cix)
-      o += part[(size_t)cix * (D + 2) + 2 + tid] * fg_exp2(part[(size_t)cix * (D + 2)] - M);
-    fg_store_out<ESIZE>(a.out, (size_t)u * D + tid, o * inv);
+  // ---- merge the chunk partials of every query head:
+  //      o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M)
+  float M = FG_NEG_BIG, inv = 0.f;   // of head 0 (the only one without grouping)
+  for (int h = 0; h < G; ++h) {
+    const float* ph = part + (size_t)h * (D + 2);
+    const size_t cs = (size_t)G * (D + 2);  // stride between chunks
+    float Mh = FG_NEG_BIG;
+    for (int cix = 0; cix < nch; ++cix) Mh = fmaxf(Mh, ph[cix * cs]);
+    float Lsum = 0.f;
+    for (int cix = 0; cix < nch; ++cix) Lsum += ph[cix * cs + 1] * fg_exp2(ph[cix * cs] - Mh);
+    const float invh = 1.0f / Lsum;
+    if (tid < D) {
+      float o = 0.f;
+      for (int cix = 0; cix < nch; ++cix) o += ph[cix * cs + 2 + tid] * fg_exp2(ph[cix * cs] - Mh);
+      fg_store_out<ESIZE>(a.out, ((size_t)u * G + h) * D + tid, o * invh);
+    }
+    if (h == 0) { M = Mh; inv = invh; }
+    if (GRP && tid == 0) { s_M[h] = Mh; s_inv[h] = invh; }
+  }
+  // Grouped heads: this step's attention on held slot j summed over the query heads (what the
+  // token's cumulative score receives) replaces head 0's logit in place, so that the rest of
+  // the kernel reads one ready value per slot (each thread only touches its own slots).
+  if (GRP) {
+    __syncthreads();
+    if (scored) {
+      for (int j = tid; j < L; j += 256) {
+        float* lgj = a.clogit + (off + j) * G;
+        float sum = 0.f;
+        for (int h = 0; h < G; ++h) sum += fg_exp2(lgj[h] - s_M[h]) * s_inv[h];
+        lgj[0] = sum;
+      }
+    }
   }
 
   if (policy >= 4 && !probing) {
@@ -245,7 +294,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         const int pj = pos[j];
         if ((cb & cmask) != 0 || pj > wlo) prot |= 1u << i;
         if (scored) {
-          lg[i] = a.clogit[off + j];
+          lg[i] = a.clogit[(off + j) * G];
           sc[i] = score[j];
         }
       }
@@ -256,7 +305,9 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
         const int j = tid + 256 * i;
         if (j < L) {
           // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
-          const float aj = fg_exp2(lg[i] - M) * inv;
+          float aj = lg[i];
+          if (GRP) asm volatile("" : "+v"(aj));  // (keeps the compiler from fusing the 24 updates: it spills otherwise)
+          else aj = fg_exp2(aj - M) * inv;
           const double v = sc[i] + (double)aj;
           score[j] = v;
           kc[i] = (uint64_t)__double_as_longlong(v);
@@ -271,7 +322,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     }
   } else if (scored) {
     for (int j = tid; j < L; j += 256) {
-      const float aj = fg_exp2(a.clogit[off + j] - M) * inv;
+      const float aj = GRP ? a.clogit[(off + j) * G] : fg_exp2(a.clogit[off + j] - M) * inv;
       score[j] += (double)aj;
     }
     __syncthreads();
@@ -283,7 +334,9 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
     // tokens among the held ones (frequent = the top-k just selected, local = last w positions)
     double r[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
     for (int j = tid; j < L; j += 256) {
-      const double aj = (double)(fg_exp2(a.clogit[off + j] - M) * inv);
+      // the mean of the G heads' rows
+      const double aj = GRP ? (double)a.clogit[(off + j) * G] / (double)G
+                            : (double)(fg_exp2(a.clogit[off + j] - M) * inv);
       const int c = cls[j];
       const bool top = fg_in_topk(tk, score[j], (uint32_t)pos[j]), recent = pos[j] > p_new - a.w;
 #pragma unroll
@@ -337,7 +390,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   }
 
   // ---- in-place release: i-th hole (evicted slot below new_len) <- i-th kept slot above it
-  int* scratch = reinterpret_cast<int*>(a.clogit + off);  // logits are dead from here on
+  int* scratch = reinterpret_cast<int*>(a.clogit + off * G);  // logits are dead from here on
   __syncthreads();
   int run_h = 0, run_m = 0;
   if (small) {
@@ -432,26 +485,36 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
 
 }  // namespace
 
-hipError_t fg_launch_decode_attn(const fg_decode_args& a, hipStream_t s) {
+template <bool GRP>
+static hipError_t launch_attn(const fg_decode_args& a, hipStream_t s) {
   const dim3 grid((unsigned)a.max_chunks), block(256);
   if (a.dtype == FG_BF16) {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<2, 128>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_partial_kernel<2, 64>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<2, 128, GRP>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<2, 64, GRP>), grid, block, 0, s, a);
   } else {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<4, 128>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_partial_kernel<4, 64>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<4, 128, GRP>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<4, 64, GRP>), grid, block, 0, s, a);
   }
   return hipGetLastError();
 }
 
-hipError_t fg_launch_decode_update(const fg_decode_args& a, hipStream_t s) {
+template <bool GRP>
+static hipError_t launch_update(const fg_decode_args& a, hipStream_t s) {
   const dim3 grid((unsigned)a.U), block(256);
   if (a.dtype == FG_BF16) {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<2, 128>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_finish_kernel<2, 64>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<2, 128, GRP>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_finish_kernel<2, 64, GRP>), grid, block, 0, s, a);
   } else {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<4, 128>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_finish_kernel<4, 64>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_finish_kernel<4, 128, GRP>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_finish_kernel<4, 64, GRP>), grid, block, 0, s, a);
   }
   return hipGetLastError();
+}
+
+hipError_t fg_launch_decode_attn(const fg_decode_args& a, hipStream_t s) {
+  return a.G > 1 ? launch_attn<true>(a, s) : launch_attn<false>(a, s);
+}
+
+hipError_t fg_launch_decode_update(const fg_decode_args& a, hipStream_t s) {
+  return a.G > 1 ? launch_update<true>(a, s) : launch_update<false>(a, s);
 }

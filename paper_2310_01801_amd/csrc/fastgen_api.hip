@@ -35,6 +35,7 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
   FG_REQUIRE(c->softmax_scale >= 0.f && isfinite(c->softmax_scale), "softmax_scale must be >= 0");
   FG_REQUIRE(c->forced_policy >= -1 && c->forced_policy <= 4, "forced_policy must be -1..4");
   FG_REQUIRE(c->cache_tokens >= 0, "cache_tokens must be >= 0");
+  FG_REQUIRE(c->group_size >= 0 && c->group_size <= 16, "group_size must be 0..16");
   bool any = false;
   for (int i = 0; i < 4; ++i) {
     FG_REQUIRE(c->family[i] >= 0 && c->family[i] <= 15, "family entries must be FG_COMP_* masks (0..15)");
@@ -55,9 +56,12 @@ void family_of(const fg_config& c, int* out) {
   for (int i = 0; i < 4; ++i) out[i] = any ? c.family[i] : eq2[i];
 }
 
+int group_of(const fg_config& c) { return c.group_size > 1 ? c.group_size : 1; }
+
 fg_layout make_layout(const fg_config& c) {
   fg_layout L;
   memset(&L, 0, sizeof(L));
+  const size_t G = (size_t)group_of(c);
   const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len, d = (size_t)c.head_dim;
   const size_t e = c.dtype == FG_BF16 ? 2 : 4;
   const size_t full = n + (size_t)c.max_new_tokens;
@@ -66,7 +70,7 @@ fg_layout make_layout(const fg_config& c) {
   L.max_chunks = (int64_t)(pool / FG_DECODE_CHUNK + U);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-  L.lse2 = take(U * n * 4);
+  L.lse2 = take(U * G * n * 4);
   L.colsum = take(U * n * 8);
   L.bandcol = take(U * n * 8);
   L.keep = take(U * n);
@@ -83,10 +87,10 @@ fg_layout make_layout(const fg_config& c) {
   L.cscore = take(pool * 8);
   L.cpos = take(pool * 4);
   L.ccls = take(pool);
-  L.clogit = take(pool * 4);
+  L.clogit = take(pool * G * 4);
   L.chunk_off = take((U + 1) * 4);
   L.item_unit = take((size_t)L.max_chunks * 32);
-  L.part = take((size_t)L.max_chunks * (d + 2) * 4);
+  L.part = take((size_t)L.max_chunks * G * (d + 2) * 4);
   L.total = o;
   return L;
 }
@@ -211,12 +215,12 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   pa.lse2 = at<float>(ctx, L.lse2);
   pa.colsum = at<double>(ctx, L.colsum);
   pa.bandcol = at<double>(ctx, L.bandcol);
-  pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w;
+  pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w; pa.G = group_of(c);
   pa.scale = ctx->scale;
   hipError_t e;
   {
     PhaseTimer tm(ctx, FG_PHASE_SWEEP1, s);
-    if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * c.prompt_len, s);
+    if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * pa.G * c.prompt_len, s);
     else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
   }
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(row log-sum-exp sweep)");
@@ -234,7 +238,7 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   sa.len = at<int32_t>(ctx, L.len);
   sa.policy_out = policy; sa.recov_out = recovery; sa.kcount_out = kept_count;
   sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
-  sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f;
+  sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f; sa.G = pa.G;
   sa.forced_policy = c.forced_policy;
   family_of(c, sa.family);
   {
@@ -305,6 +309,7 @@ static fg_status decode_step_impl(fastgen_ctx* ctx, const void* q, const void* k
   da.part = at<float>(ctx, L.part);
   da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;
   da.units_per_seq = c.num_units / c.num_seqs; da.w = ctx->w; da.step = ctx->steps_done;
+  da.G = group_of(c);
   da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks;
   da.probe = probe;
   family_of(c, da.family);

@@ -13,7 +13,7 @@
 // Every region starts on a 256-byte boundary. Offsets are in bytes from the workspace base.
 struct fg_layout {
   // profiling scratch
-  size_t lse2;      // [U, n] float   row log2-sum-exp2 of the scaled logits
+  size_t lse2;      // [U * G, n] float   row log2-sum-exp2 of the scaled logits, per query head
   size_t colsum;    // [U, n] double  cumulative attention score of every prompt token
   size_t bandcol;   // [U, n] double  the part of colsum inside the local band
   size_t keep;      // [U, n] uint8   0 = dropped, else 4 | class bits of the kept token
@@ -32,11 +32,11 @@ struct fg_layout {
   size_t cscore;    // [pool] double
   size_t cpos;      // [pool] int32
   size_t ccls;      // [pool] uint8
-  size_t clogit;    // [pool] float   this step's scaled logit of every held token
+  size_t clogit;    // [pool, G] float   this step's scaled logit of every held token, per query head
   // decode scratch
   size_t chunk_off; // [U + 1] int32  first chunk of each unit in the flat work list
   size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, 1, pool offset lo/hi, 0, 0
-  size_t part;      // [max_chunks, d + 2] float  split-KV partial (max, sum, o)
+  size_t part;      // [max_chunks, G, d + 2] float  split-KV partial (max, sum, o) per query head
   size_t total;
   int64_t pool_tokens;
   int64_t max_chunks;
@@ -65,6 +65,7 @@ struct fg_profile_args {
   const void* Q; const void* K;
   float* lse2; double* colsum; double* bandcol;
   int U, n, d, w;
+  int G;  // query heads per K/V unit: Q and lse2 hold U * G units
   float scale;
 };
 
@@ -73,7 +74,7 @@ struct fg_select_args {
   uint8_t* keep; int32_t* slot;
   int32_t* policy; double* recov; int32_t* kcount; int32_t* cap; int32_t* len;
   int32_t* policy_out; double* recov_out; int32_t* kcount_out;  // optional caller copies
-  int U, n, units_per_seq, w, S;
+  int U, n, units_per_seq, w, S, G;
   double T, r_f;
   int forced_policy;
   int family[4];  // FG_COMP_* mask of policy ids 0..3 (0 = unused id)
@@ -93,7 +94,7 @@ struct fg_decode_args {
   const int32_t* policy; const int32_t* cap; const int64_t* off; int32_t* len; int32_t* flags;
   void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; float* clogit;
   const int32_t* chunk_off; const int32_t* item_unit; float* part;
-  int U, n, d, dtype, units_per_seq, w, step;
+  int U, n, d, dtype, units_per_seq, w, step, G;
   int family[4];   // FG_COMP_* mask of policy ids 0..3 (stability probe)
   double* probe;   // NULL, or [U, 5]: this step's attention mass on every family member
   double r_f;

@@ -13,16 +13,20 @@ constexpr int kTile = 32;
 template <int D, int PASS>
 __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, float* __restrict__ lse2,
-    double* __restrict__ colsum, double* __restrict__ bandcol, int n, int w, float c, int nblk) {
+    double* __restrict__ colsum, double* __restrict__ bandcol, int n, int w, float c, int nblk,
+    int G) {
   __shared__ __attribute__((aligned(16))) float tile[kTile][D];
   __shared__ float lse_t[kTile];
 
   const int unit = blockIdx.x / nblk, tid = threadIdx.x;
   const int WG0 = (blockIdx.x % nblk) * 256;
   const int own = WG0 + tid;
-  const size_t base = (size_t)unit * (size_t)n * D;
-  const float* own_mat = (PASS == 1 ? Q : K) + base;
-  const float* str_mat = (PASS == 1 ? K : Q) + base;
+  // G query heads share a K/V unit: sweep 1 runs per query head (unit = u * G + g) against
+  // K of u; sweep 2 runs per K/V unit and streams the rows of its G query heads in turn
+  const size_t mat = (size_t)n * D;
+  const float* own_mat = (PASS == 1 ? Q : K) + (size_t)unit * mat;
+  const float* str_base = (PASS == 1) ? K + (size_t)(unit / G) * mat : Q + (size_t)unit * G * mat;
+  const float* lse_base = lse2 + (size_t)unit * (PASS == 1 ? 1 : G) * n;
 
   float o[D];
 #pragma unroll
@@ -39,6 +43,10 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
   float m_run = FG_NEG_BIG;
   double l_run = 0.0, col_acc = 0.0, band_acc = 0.0;
 
+  const int heads = (PASS == 1) ? 1 : G;
+  for (int h = 0; h < heads; ++h) {
+  const float* str_mat = str_base + (size_t)h * mat;
+  const float* lse_row = lse_base + (size_t)h * n;
   for (int t = t_begin; t < t_end; ++t) {
     const int t0 = t * kTile;
     __syncthreads();
@@ -48,7 +56,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
       if (t0 + item < n) v = *reinterpret_cast<const f32x4*>(str_mat + (size_t)(t0 + item) * D + ch * 4);
       *reinterpret_cast<f32x4*>(&tile[item][ch * 4]) = v;
     }
-    if (PASS == 2 && tid < kTile) lse_t[tid] = (t0 + tid < n) ? lse2[(size_t)unit * n + t0 + tid] : 0.f;
+    if (PASS == 2 && tid < kTile) lse_t[tid] = (t0 + tid < n) ? lse_row[t0 + tid] : 0.f;
     __syncthreads();
     if (own >= n) continue;
     for (int it = 0; it < kTile; ++it) {
@@ -71,6 +79,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
       }
     }
   }
+  }
   if (own < n) {
     if (PASS == 1) lse2[(size_t)unit * n + own] = m_run + (float)log2(l_run);
     else {
@@ -83,16 +92,16 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
 template <int D>
 hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const int nblk = (a.n + 255) / 256;
-  const dim3 grid((unsigned)((size_t)nblk * a.U)), block(256);
+  const dim3 grid((unsigned)((size_t)nblk * a.U * (pass == 1 ? a.G : 1))), block(256);
   const float c = a.scale * FG_LOG2E;
   const float* Q = static_cast<const float*>(a.Q);
   const float* K = static_cast<const float*>(a.K);
   if (pass == 1)
     hipLaunchKernelGGL((fg_profile_f32_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                       a.bandcol, a.n, a.w, c, nblk);
+                       a.bandcol, a.n, a.w, c, nblk, a.G);
   else
     hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                       a.bandcol, a.n, a.w, c, nblk);
+                       a.bandcol, a.n, a.w, c, nblk, a.G);
   return hipGetLastError();
 }
 

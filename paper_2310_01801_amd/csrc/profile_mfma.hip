@@ -34,7 +34,7 @@ template <int D, int PASS>
 __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
     const __bf16* __restrict__ Q, const __bf16* __restrict__ K, float* __restrict__ lse2,
     double* __restrict__ colsum, double* __restrict__ bandcol, int U, int n, int w, float c,
-    int nblk) {
+    int nblk, int G) {
   constexpr int KK = D / 16;
   constexpr int RS = Lds<D>::kRowBytes;
   constexpr int CHUNKS_PER_ROW = D / 8;                    // 16-byte chunks per item
@@ -55,10 +55,14 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keep it scalar
   const int ln = lane & 31, lh = lane >> 5;
-  const size_t base = (size_t)unit * (size_t)n * D;
-  const __bf16* own_mat = (PASS == 1 ? Q : K) + base;
-  const __bf16* str_mat = (PASS == 1 ? K : Q) + base;
-  const float* lse_row = lse2 + (size_t)unit * n;
+  // G query heads share a K/V unit. Sweep 1 runs per query head (U counts query heads, unit =
+  // u * G + g) against the keys of u; sweep 2 runs per K/V unit and streams the query rows of
+  // its G heads one after the other (heads are contiguous: one buffer covers them all).
+  const size_t mat = (size_t)n * D;
+  const __bf16* own_mat = (PASS == 1 ? Q : K) + (size_t)unit * mat;
+  const __bf16* str_mat = (PASS == 1) ? K + (size_t)(unit / G) * mat : Q + (size_t)unit * G * mat;
+  const float* lse_row = lse2 + (size_t)unit * (PASS == 1 ? 1 : G) * n;
+  const int heads = (PASS == 1) ? 1 : G;
 
   const int WG0 = blk * kOwnPerBlock;       // first owner item of the workgroup
   const int O0 = WG0 + wave * kOwnPerWave;  // first owner item of the wave
@@ -90,9 +94,9 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   // tile offset is a scalar, and rows past the end of the unit read as zeros (every use of
   // them is masked), so a load costs no vector-ALU instruction.
   const __amdgpu_buffer_rsrc_t str_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(str_mat), 0, n * D * 2, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(str_mat), 0, heads * n * D * 2, 0x00020000);
   const __amdgpu_buffer_rsrc_t lse_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_row), 0, n * 4, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_row), 0, heads * n * 4, 0x00020000);
   int voff[LOADS];
 #pragma unroll
   for (int r = 0; r < LOADS; ++r) {
@@ -102,12 +106,14 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   const int voff_lse = (tid & (kTile - 1)) * 4;
   u32x4 stage[LOADS];
   float stage_lse = 0.f;
-  auto gload = [&](int t) {
-    const int t0 = t * kTile;
+  // `row0` = first streamed row of the tile counted over all heads (head * n + t * 32); a tile
+  // that runs past its head's last row reads the next head's rows (or zeros after the last
+  // head): those rows are masked wherever they are used.
+  auto gload = [&](int row0) {
 #pragma unroll
     for (int r = 0; r < LOADS; ++r)
-      stage[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(str_rsrc, voff[r], t0 * (D * 2), 0));
-    if (PASS == 2) stage_lse = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lse_rsrc, voff_lse, t0 * 4, 0));
+      stage[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(str_rsrc, voff[r], row0 * (D * 2), 0));
+    if (PASS == 2) stage_lse = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lse_rsrc, voff_lse, row0 * 4, 0));
   };
   auto lstore = [&](int buf) {
 #pragma unroll
@@ -125,19 +131,23 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 
   // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards, so that the
   // workgroups of one unit stream the same tiles at the same time, measured 25 % slower).
-  const int n_it = t_end - t_begin;
-  auto tile_of = [&](int it) { return t_begin + it; };
+  const int nt = t_end - t_begin;     // tiles per head
+  const int n_it = nt * heads;
   if (n_it > 0) {
-    gload(tile_of(0));
+    gload(t_begin * kTile);
     lstore(0);
   }
   __syncthreads();
 
+  int t = t_begin, head_row0 = 0;     // current tile and first row of the current head
   for (int it = 0; it < n_it; ++it) {
     const int buf = it & 1;
-    const int t = tile_of(it);
     const int t0 = t * kTile;
-    gload(tile_of(min(it + 1, n_it - 1)));  // unconditional: the load count per iteration is static
+    // next tile: the following one of this head, else the first one of the next head
+    int t_next = t + 1, head_next = head_row0;
+    if (t_next == t_end) { t_next = t_begin; head_next += n; }
+    // unconditional (the load count per iteration is static); the last iteration re-reads its own tile
+    gload(it + 1 < n_it ? head_next + t_next * kTile : head_row0 + t0);
 
     // what this wave has to do with the tile, per owner fragment
     bool need[2];
@@ -247,6 +257,8 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 
     lstore(buf ^ 1);
     __syncthreads();
+    t = t_next;
+    head_row0 = head_next;
   }
 
   // ---- merge the two half-waves and store
@@ -277,17 +289,18 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 template <int D>
 hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const int nblk = (a.n + kOwnPerBlock - 1) / kOwnPerBlock;
-  const int ugroups = (a.U + 7) / 8;
+  const int units = (pass == 1) ? a.U * a.G : a.U;  // sweep 1: one unit per query head
+  const int ugroups = (units + 7) / 8;
   const dim3 grid((unsigned)(8 * nblk * ugroups)), block(256);
   const float c = a.scale * FG_LOG2E;
   const __bf16* Q = static_cast<const __bf16*>(a.Q);
   const __bf16* K = static_cast<const __bf16*>(a.K);
   if (pass == 1)
     hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                       a.bandcol, a.U, a.n, a.w, c, nblk);
+                       a.bandcol, units, a.n, a.w, c, nblk, a.G);
   else
     hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
-                       a.bandcol, a.U, a.n, a.w, c, nblk);
+                       a.bandcol, units, a.n, a.w, c, nblk, a.G);
   return hipGetLastError();
 }
 

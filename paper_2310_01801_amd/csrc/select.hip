@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
   double R[5];
   int C[5], CC[4];
   for (int c = 0; c < 4; ++c) {
-    R[c] = fg_block_sum_f64(r[c], dred) / (double)n;
+    R[c] = fg_block_sum_f64(r[c], dred) / ((double)n * (double)a.G);  // mean over the rows of all G query heads
     C[c] = fg_block_sum_i32(cnt[c], ired);
     CC[c] = fg_block_sum_i32(ccnt[c], ired);
   }

@@ -251,6 +251,37 @@ def decode_unit(w: Workload, plan: UnitPlan, cls_decode: np.ndarray, u: int, dev
     return q.to(dt), k.to(dt), v.to(dt)
 
 
+def prompt_group_queries(w: Workload, plan: UnitPlan, cls_prompt: np.ndarray, u: int, G: int,
+                         device="cpu") -> torch.Tensor:
+    """Q [G, n, d]: the query heads that share K/V head u. Head 0 is prompt_unit's Q; the
+    others draw fresh noise and carry the same planted dimensions (same attention pattern)."""
+    n, d = w.prompt_len, w.head_dim
+    out = torch.empty((G, n, d), dtype=w.torch_dtype, device=device)
+    out[0] = prompt_unit(w, plan, cls_prompt, u, device)[0]
+    b = u // w.units_per_seq
+    pos = torch.arange(n, device=device)
+    for h in range(1, G):
+        Q = torch.randn((n, d), generator=_gen(device, w.seed, 23, u, h), device=device, dtype=torch.float32)
+        _plant(w, plan, u, Q, torch.empty_like(Q), pos, torch.as_tensor(cls_prompt[b], device=device))
+        out[h] = Q.to(w.torch_dtype)
+    return out
+
+
+def decode_group_queries(w: Workload, plan: UnitPlan, cls_decode: np.ndarray, u: int, G: int,
+                         device="cpu") -> torch.Tensor:
+    """q [S, G, d] for the decode steps, head 0 = decode_unit's q."""
+    n, S, d = w.prompt_len, w.steps, w.head_dim
+    out = torch.empty((S, G, d), dtype=w.torch_dtype, device=device)
+    out[:, 0] = decode_unit(w, plan, cls_decode, u, device)[0]
+    b = u // w.units_per_seq
+    pos = torch.arange(n, n + S, device=device)
+    for h in range(1, G):
+        q = torch.randn((S, d), generator=_gen(device, w.seed, 24, u, h), device=device, dtype=torch.float32)
+        _plant(w, plan, u, q, torch.empty_like(q), pos, torch.as_tensor(cls_decode[:, b], device=device))
+        out[:, h] = q.to(w.torch_dtype)
+    return out
+
+
 def prompt_batch(w: Workload, plan: UnitPlan, cls_prompt: np.ndarray, units: Sequence[int],
                  device="cpu") -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
     """Q, K, V [len(units), n, d] for the given units."""

@@ -61,7 +61,7 @@ class GpuRun:
 
     def __init__(self, w: synth.Workload, units: Sequence[int], device="cuda:0",
                  forced_policy: int = -1, gen_device: Optional[str] = None, cache_tokens: int = 0,
-                 family: Optional[Sequence[int]] = None):
+                 family: Optional[Sequence[int]] = None, group_size: int = 1):
         self.w, self.units, self.device = w, list(units), device
         gen_device = gen_device or device
         self.plan = synth.unit_plan(w)
@@ -69,14 +69,21 @@ class GpuRun:
         m = len(self.units)
         self.Q, self.K, self.V = (t.to(device) for t in
                                   synth.prompt_batch(w, self.plan, self.cls_prompt, self.units, gen_device))
+        self.G = G = group_size
+        if G > 1:   # [m * G, n, d]: the G query heads of every K/V unit, head 0 = the unit's own Q
+            self.Q = torch.cat([synth.prompt_group_queries(w, self.plan, self.cls_prompt, u, G, gen_device)
+                                for u in self.units]).to(device)
         seqs = [u // w.units_per_seq for u in self.units]
         self.cls_u = torch.from_numpy(self.cls_prompt[seqs].copy()).to(device)          # [m, n]
         self.cls_dec_u = torch.from_numpy(self.cls_decode[:, seqs].copy()).to(device)   # [S, m]
         if w.steps > 0:
             self.q, self.k, self.v = (t.to(device) for t in
                                       synth.decode_batch(w, self.plan, self.cls_decode, self.units, gen_device))
+            if G > 1:   # [S, m * G, d]
+                self.q = torch.cat([synth.decode_group_queries(w, self.plan, self.cls_decode, u, G, gen_device)
+                                    for u in self.units], dim=1).to(device).contiguous()
         cfg = binding.make_config(m, m, w.head_dim, w.torch_dtype, w.prompt_len, w.steps, w.T, w.r_l,
-                                  w.r_f, 0.0, forced_policy, cache_tokens, family)
+                                  w.r_f, 0.0, forced_policy, cache_tokens, family, group_size)
         self.fg = binding.FastGen(cfg, device)
         self.forced = forced_policy
         self.family = tuple(family) if family is not None else fo.DEFAULT_FAMILY
@@ -114,9 +121,12 @@ def oracle_unit(run: GpuRun, i: int, steps: Optional[int] = None, record_states:
     S = w.steps if steps is None else steps
     f64 = synth.to_f64
     cls = run.cls_u[i].cpu().numpy()
-    args = (f64(run.Q[i]), f64(run.K[i]), f64(run.V[i]), cls)
+    G = run.G
+    Qi = f64(run.Q[i]) if G == 1 else f64(run.Q[i * G:(i + 1) * G])
+    args = (Qi, f64(run.K[i]), f64(run.V[i]), cls)
     if S > 0:
-        dec = (f64(run.q[:S, i]), f64(run.k[:S, i]), f64(run.v[:S, i]), run.cls_dec_u[:S, i].cpu().numpy())
+        qi = f64(run.q[:S, i]) if G == 1 else f64(run.q[:S, i * G:(i + 1) * G])
+        dec = (qi, f64(run.k[:S, i]), f64(run.v[:S, i]), run.cls_dec_u[:S, i].cpu().numpy())
     else:
         dec = (None, None, None, None)
     return fo.run_unit(*args, *dec, w.T, w.r_l, w.r_f, scale_of(w), forced_policy=run.forced,
@@ -204,7 +214,8 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
             if fs >= 0 and t >= fs and i not in fragile_from:
                 fragile_from[i] = fs
                 rep.tie_fragile_decode += 1
-            err = float(np.max(np.abs(out[i] - o_ref)))
+            o_gpu = out[i] if run.G == 1 else out[i * run.G:(i + 1) * run.G]
+            err = float(np.max(np.abs(o_gpu - o_ref)))
             rep.max_out_err = max(rep.max_out_err, err)
             assert err <= tol, f"unit {run.units[i]} step {t}: |o - oracle| = {err:.3e} > {tol}"
             if rho is not None:

@@ -51,9 +51,11 @@ def test_workspace_bytes_and_validation(lib):
     assert nbytes > 8 * 68 * 128 * 2 * 2 and nbytes % 256 == 0
     assert binding.fastgen_workspace_bytes(_cfg(cache_tokens=100)) < nbytes
     assert binding.fastgen_workspace_bytes(_cfg(family=(8, 4, 12, 0), forced_policy=2)) == nbytes
+    assert binding.fastgen_workspace_bytes(_cfg(group_size=4)) > nbytes   # per-head lse, logits, partials
+    assert binding.fastgen_workspace_bytes(_cfg(group_size=0)) == nbytes
     for bad in (dict(head_dim=96), dict(num_seqs=3), dict(T=0.0), dict(T=1.5), dict(r_l=-0.1),
                 dict(prompt_len=0), dict(forced_policy=7), dict(num_units=0), dict(family=(1, 16, 0, 0)),
-                dict(family=(1, 0, 0, 8), forced_policy=1)):
+                dict(family=(1, 0, 0, 8), forced_policy=1), dict(group_size=17), dict(group_size=-1)):
         assert binding.fastgen_workspace_bytes(_cfg(**bad)) == 0, bad
 
 

@@ -243,3 +243,29 @@ def test_decode_step_probe_needs_output_buffer():
     st = fg.lib.fastgen_decode_step_probe(fg._ctx, run.q[0].data_ptr(), run.k[0].data_ptr(), run.v[0].data_ptr(),
                                           run.cls_dec_u[0].data_ptr(), run.q[0].data_ptr(), None, None)
     assert st == 1  # FG_EINVAL, nothing launched
+
+
+# Grouped query heads (extension; the paper names grouped-query attention future work): G query
+# heads share one K/V head, its cache and its policy.
+@pytest.mark.parametrize("G,d,dtype,n,S", [
+    (2, 128, "bf16", 300, 24),
+    (4, 64, "f32", 97, 10),
+    (8, 128, "bf16", 520, 16),
+    (3, 64, "bf16", 200, 12),
+])
+def test_grouped_query_heads(G, d, dtype, n, S):
+    w = W["llama7b_b1"].scaled(name=f"gqa{G}", layers=1, heads=10, batch=2, prompt_len=n, steps=S, head_dim=d,
+                               dtype=dtype, seed=70 + G)
+    run = H.GpuRun(w, range(w.num_units), group_size=G)
+    rep = H.compare(run, probe_steps=[1, S - 1])
+    _report(f"grouped heads G={G} d={d} {dtype}", rep)
+    assert rep.units == 20
+
+
+@pytest.mark.parametrize("policy", [2, 3, 4])
+def test_grouped_query_heads_forced_policy(policy):
+    w = W["llama7b_b1"].scaled(name="gqaf", layers=1, heads=6, batch=1, prompt_len=700, steps=20, seed=77)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=policy, group_size=4)
+    rep = H.compare(run)
+    _report(f"grouped heads G=4 forced policy {policy}", rep)
+    assert rep.policies == {policy: 6}
