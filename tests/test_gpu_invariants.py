@@ -1,0 +1,93 @@
+"""GPU checks that need no oracle: properties that hold at any size, evaluated for EVERY unit of
+a BASELINE configuration at full size, in the launch configuration the benchmark uses. They
+complement the sampled element-by-element comparison with the float64 oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2310_01801_amd import synth  # noqa: E402
+import fg_harness as H  # noqa: E402
+
+W = synth.WORKLOADS
+
+
+def _first_hit(rec, T):
+    ok = rec[:, :4] >= T
+    return np.where(ok.any(axis=1), ok.argmax(axis=1), 4)
+
+
+@pytest.mark.parametrize("name,steps", [("llama7b_b1", 6), ("llama7b_b16", 3)])
+def test_every_unit_at_full_size(name, steps):
+    w = W[name].scaled(steps=steps)
+    n, U, T = w.prompt_len, w.num_units, w.T
+    run = H.GpuRun(w, range(U))
+    pol, rec, cnt = run.profile_and_compact()
+    cls = run.cls_u                       # [U, n] on the device
+    wloc, k_f = max(1, math.floor(w.r_l * n)), math.floor(w.r_f * n)
+
+    # recoveries: in [0, 1], nested family -> monotone, C_full = 1; Eq. 1 on the returned doubles
+    assert np.all(rec[:, 4] == 1.0) and np.all(rec >= 0.0) and np.all(rec <= 1.0 + 1e-9)
+    assert np.all(np.diff(rec[:, :4], axis=1) >= -1e-12)
+    assert np.array_equal(pol, _first_hit(rec, T))
+    # kept counts against the class rows and the budgets
+    n_special = ((cls & 1) != 0).sum(dim=1).cpu().numpy()
+    n_class = ((cls & 3) != 0).sum(dim=1).cpu().numpy()
+    assert np.array_equal(cnt[:, 0], n_special) and np.array_equal(cnt[:, 1], n_class)
+    assert np.all(cnt[:, 2] >= np.maximum(n_class, k_f)) and np.all(cnt[:, 2] <= n_class + k_f)
+    assert np.all(cnt[:, 3] >= cnt[:, 2]) and np.all(cnt[:, 3] <= cnt[:, 2] + wloc) and np.all(cnt[:, 4] == n)
+
+    def check_state(t_done):
+        st = run.fg.fastgen_export_state(rows=True)
+        assert int(st["status"].item()) == 0
+        lengths, off, pos, sc = st["lengths"].long(), st["offsets"], st["positions"].long(), st["scores"]
+        unit_of = torch.repeat_interleave(torch.arange(U, device=pos.device), lengths)
+        # ascending, unique, in range
+        same_unit = unit_of[1:] == unit_of[:-1]
+        assert bool(torch.all(pos[1:][same_unit] > pos[:-1][same_unit]))
+        assert bool(torch.all(pos >= 0)) and bool(torch.all(pos < n + t_done))
+        # what each policy must hold: special always; punctuation from policy 1; the window for 3; all for 4
+        polt = torch.as_tensor(pol, device=pos.device)
+        all_cls = cls if t_done == 0 else torch.cat([cls, run.cls_dec_u[:t_done].T.contiguous()], dim=1)
+        held = torch.zeros((U, n + t_done), dtype=torch.bool, device=pos.device)
+        held[unit_of, pos] = True
+        need = (all_cls & 1) != 0
+        need = need | (((all_cls & 2) != 0) & (polt >= 1)[:, None])
+        recent = torch.arange(n + t_done, device=pos.device)[None, :] > (n + t_done - 1 - wloc)
+        need = need | (recent & (polt == 3)[:, None]) | (polt == 4)[:, None]
+        assert bool(torch.all(held[need])), "a token its policy must keep is missing"
+        only_class = (polt <= 1)
+        assert bool(torch.all(held[only_class] == need[only_class])), "a class-only head holds something else"
+        return lengths, off, pos, sc, unit_of, st
+
+    lengths, off, pos, sc, unit_of, st = check_state(0)
+    assert np.array_equal(lengths.cpu().numpy(), cnt[np.arange(U), pol])
+    # compacted rows are the source rows; compacted scores sum to what the policy recovers
+    assert torch.equal(st["keys"], run.K[unit_of, pos]) and torch.equal(st["values"], run.V[unit_of, pos])
+    kept_mass = torch.zeros(U, dtype=torch.float64, device=pos.device).index_add_(0, unit_of, sc).cpu().numpy() / n
+    stat = pol <= 2
+    assert np.allclose(kept_mass[stat], rec[stat, pol[stat]], atol=1e-9)
+    # (a head on the local policy also recovers band mass of columns it no longer holds)
+    assert np.allclose(kept_mass[pol == 4], 1.0, atol=2e-6)      # rows of A sum to 1
+
+    # decode: full-cache heads against plain PyTorch attention over everything; all heads finite
+    full = np.nonzero(pol == 4)[0]
+    fidx = torch.as_tensor(full, device=pos.device)
+    scale = 1.0 / math.sqrt(w.head_dim)
+    for t in range(steps):
+        out = run.step(t).float()
+        assert bool(torch.isfinite(out).all())
+        if full.size:
+            Kf = torch.cat([run.K[fidx], run.k[:t + 1, fidx].transpose(0, 1)], dim=1).float()
+            Vf = torch.cat([run.V[fidx], run.v[:t + 1, fidx].transpose(0, 1)], dim=1).float()
+            a = torch.softmax(torch.einsum("ud,uld->ul", run.q[t, fidx].float(), Kf) * scale, dim=1)
+            ref = torch.einsum("ul,uld->ud", a, Vf)
+            assert float((out[fidx] - ref).abs().max()) < 2e-2
+    lengths, *_ = check_state(steps)
+    ln = lengths.cpu().numpy()
+    assert np.all(ln[pol == 4] == n + steps) and np.all(ln <= n + steps) and np.all(ln >= n_special)
+    print(f"\n[invariants] {name}: {U} units, policies {np.bincount(pol, minlength=5).tolist()}, "
+          f"held tokens after {steps} steps: mean {ln.mean():.0f}", flush=True)
