@@ -269,3 +269,15 @@ def test_grouped_query_heads_forced_policy(policy):
     rep = H.compare(run)
     _report(f"grouped heads G=4 forced policy {policy}", rep)
     assert rep.policies == {policy: 6}
+
+
+def test_runs_on_a_side_stream():
+    # every kernel goes to the caller's stream: run the whole path on a non-default stream
+    w = W["llama7b_b1"].scaled(name="stream", layers=1, heads=8, batch=1, prompt_len=260, steps=10, seed=91)
+    side = torch.cuda.Stream()
+    run = H.GpuRun(w, range(w.num_units))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        rep = H.compare(run, probe_steps=[3])
+    side.synchronize()
+    _report("side stream", rep)
