@@ -47,9 +47,9 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   constexpr int TPW = CH / 4;          // tokens per wave
   constexpr int ITERS = TPW / TPL;     // loads per wave for its tokens
   __shared__ float s_red[8];
-  __shared__ float s_o[4][D];
+  __shared__ float s_o[GRP ? 1 : 4][D];
 
-  // header: everything static comes from one 32-byte record; only the length is looked up
+  // header: one 32-byte record per item carries everything, the unit's current length included
   const int item = blockIdx.x;
   const int n_items = a.chunk_off[a.U];
   const int overflow = a.flags[0];
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   const int2 rec_off = *reinterpret_cast<const int2*>(a.item_unit + (size_t)item * 8 + 4);
   if (overflow != 0 || item >= n_items) return;
   const int u = rec.x, chunk = rec.y;
-  const int Lold = a.len[u], L = Lold + 1;
+  const int Lold = rec.w, L = Lold + 1;
   const int start = chunk * CH;
   if (start >= L) return;
   if (L > rec.z) {  // cannot happen while the host bounds the step count
@@ -116,20 +116,84 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
     vv[it] = vw;
   }
 
-  for (int h = 0; h < G; ++h) {
   if (GRP) {
-    if (h == 0) __syncthreads();
-    const u32x4 t = *reinterpret_cast<const u32x4*>(&s_q[h * RB + g * 16]);
-    fg_unpack<ESIZE>(t, qv);
-  }
-  if (GRP) {
-    // keep the cache rows packed across the head loop (unpacking them once for all heads would
-    // need twice the register file)
+    // ---- grouped heads: each wave keeps its own (max, sum, o) per head for its tokens, so the
+    // head loop has no workgroup barrier; the four waves are merged once at the end.
+    __shared__ float s_wp[4][16][D + 2];
+    __syncthreads();  // s_q is complete
+    for (int h = 0; h < G; ++h) {
+      {
+        const u32x4 t = *reinterpret_cast<const u32x4*>(&s_q[h * RB + g * 16]);
+        fg_unpack<ESIZE>(t, qv);
+      }
+      // keep the cache rows packed across the head loop (unpacking them once for all heads
+      // would need twice the register file)
 #pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-      asm volatile("" : "+v"(kv[it]), "+v"(vv[it]));
+      for (int it = 0; it < ITERS; ++it) {
+        asm volatile("" : "+v"(kv[it]), "+v"(vv[it]));
+      }
+      float x[ITERS];
+      float mw = FG_NEG_BIG;
+#pragma unroll
+      for (int it = 0; it < ITERS; ++it) {
+        float kf[EPL];
+        fg_unpack<ESIZE>(kv[it], kf);
+        float dot = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+        dot = fg_group_sum<LPR>(dot);
+        const int tok = wave * TPW + it * TPL + sub;
+        const bool ok = tok < cnt;
+        x[it] = ok ? dot * c : FG_NEG_BIG;
+        if (ok && g == 0) a.clogit[(off + start + tok) * G + h] = x[it];
+        mw = fmaxf(mw, x[it]);
+      }
+      mw = fg_wave_max(mw);
+      float lsum = 0.f;
+      float oacc[EPL];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) oacc[e] = 0.f;
+#pragma unroll
+      for (int it = 0; it < ITERS; ++it) {
+        const int tok = wave * TPW + it * TPL + sub;
+        const float p = (tok < cnt) ? fg_exp2(x[it] - mw) : 0.f;
+        lsum += p;
+        float vf[EPL];
+        fg_unpack<ESIZE>(vv[it], vf);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) oacc[e] = fmaf(p, vf[e], oacc[e]);
+      }
+#pragma unroll
+      for (int m = LPR; m < 64; m <<= 1) {
+        lsum += __shfl_xor(lsum, m, 64);
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) oacc[e] += __shfl_xor(oacc[e], m, 64);
+      }
+      if (sub == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) s_wp[wave][h][2 + g * EPL + e] = oacc[e];
+      }
+      if (lane == 0) { s_wp[wave][h][0] = mw; s_wp[wave][h][1] = lsum; }
     }
+    __syncthreads();
+    for (int h = 0; h < G; ++h) {
+      const float m0 = s_wp[0][h][0], m1 = s_wp[1][h][0], m2 = s_wp[2][h][0], m3 = s_wp[3][h][0];
+      const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+      // a wave without tokens carries the lowest max and zero sums: its factor is 0
+      const float f0 = fg_exp2(m0 - M), f1 = fg_exp2(m1 - M), f2 = fg_exp2(m2 - M), f3 = fg_exp2(m3 - M);
+      float* part = a.part + ((size_t)item * G + h) * (D + 2);
+      if (tid < D)
+        part[2 + tid] = (s_wp[0][h][2 + tid] * f0 + s_wp[1][h][2 + tid] * f1) +
+                        (s_wp[2][h][2 + tid] * f2 + s_wp[3][h][2 + tid] * f3);
+      if (tid == 0) {
+        part[0] = M;
+        part[1] = (s_wp[0][h][1] * f0 + s_wp[1][h][1] * f1) + (s_wp[2][h][1] * f2 + s_wp[3][h][1] * f3);
+      }
+    }
+    return;
   }
+
+  // ---- one query head per unit
   // scaled logits (log2 domain): x = c * q.k, one value per token shared by its LPR lanes
   float x[ITERS];
   float mx = FG_NEG_BIG;
@@ -140,16 +204,14 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
     float dot = 0.f;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
-#pragma unroll
-    for (int m = 1; m < LPR; m <<= 1) dot += __shfl_xor(dot, m, 64);
+    dot = fg_group_sum<LPR>(dot);
     const int tok = wave * TPW + it * TPL + sub;
     const bool ok = tok < cnt;
     x[it] = ok ? dot * c : FG_NEG_BIG;
-    if (ok && g == 0) a.clogit[(off + start + tok) * G + h] = x[it];
+    if (ok && g == 0) a.clogit[off + start + tok] = x[it];
     mx = fmaxf(mx, x[it]);
   }
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) mx = fmaxf(mx, __shfl_xor(mx, m, 64));
+  mx = fg_wave_max(mx);
   if (lane == 0) s_red[wave] = mx;
   __syncthreads();
   const float M = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
@@ -181,13 +243,11 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   }
   if (lane == 0) s_red[4 + wave] = lsum;
   __syncthreads();
-  float* part = a.part + ((size_t)item * G + h) * (D + 2);
+  float* part = a.part + (size_t)item * (D + 2);
   if (tid < D) part[2 + tid] = (s_o[0][tid] + s_o[1][tid]) + (s_o[2][tid] + s_o[3][tid]);
   if (tid == 0) {
     part[0] = M;
     part[1] = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
-  }
-  if (h + 1 < G) __syncthreads();  // the reduction scratch is reused by the next head
   }
 }
 
@@ -224,6 +284,11 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
   const int nch = (L + CH - 1) / CH;
+  // the new length goes to len[] and into every work-item record of the unit
+  auto set_len = [&](int v) {
+    if (tid == 0) a.len[u] = v;
+    for (int i = tid; i < (cap + CH - 1) / CH; i += 256) a.item_unit[(size_t)(c_off + i) * 8 + 3] = v;
+  };
   const float* part = a.part + (size_t)c_off * G * (D + 2);
 
   // ---- merge the chunk partials of every query head:
@@ -261,7 +326,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   }
 
   if (policy >= 4 && !probing) {
-    if (tid == 0) a.len[u] = L;
+    set_len(L);
     return;
   }
   const int p_new = a.n + a.step;
@@ -354,7 +419,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
       if (tid == 0) a.probe[(size_t)u * 5 + p] = t;
     }
     if (policy >= 4) {
-      if (tid == 0) a.len[u] = L;
+      set_len(L);
       return;
     }
   }
@@ -385,7 +450,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   }
   const int new_len = fg_block_sum_i32(mine, ired);
   if (new_len == L) {
-    if (tid == 0) a.len[u] = L;
+    set_len(L);
     return;
   }
 
@@ -480,7 +545,7 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
       }
     }
   }
-  if (tid == 0) a.len[u] = new_len;
+  set_len(new_len);
 }
 
 }  // namespace

@@ -259,7 +259,7 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   const fg_config& c = ctx->cfg;
   const fg_layout& L = ctx->lay;
   PhaseTimer tm(ctx, FG_PHASE_COMPACT, s);
-  hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int64_t>(ctx, L.off),
+  hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int32_t>(ctx, L.len), at<int64_t>(ctx, L.off),
                                    at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
                                    at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
                                    L.max_chunks, s);

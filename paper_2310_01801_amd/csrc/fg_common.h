@@ -34,6 +34,44 @@ __device__ __forceinline__ double fg_shfl_xor_f64(double v, int mask) {
   return __hiloint2double(hi, lo);
 }
 
+// ---- cross-lane reductions on the data-parallel-primitive path of the vector ALU (no LDS
+// round trip): lane i combines with a lane of its own row of 16.
+template <int CTRL>
+__device__ __forceinline__ float fg_dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+constexpr int FG_DPP_XOR1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int FG_DPP_XOR2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int FG_DPP_HALF_MIRROR = 0x141; // lane i <-> 7 - i within 8 lanes
+constexpr int FG_DPP_MIRROR = 0x140;      // lane i <-> 15 - i within 16 lanes
+
+// Sum over aligned groups of N consecutive lanes (N = 1, 2, 4, 8, 16, 32, 64); every lane of the
+// group receives the total. Fixed order: deterministic.
+template <int N>
+__device__ __forceinline__ float fg_group_sum(float v) {
+  if (N >= 2) v += fg_dpp<FG_DPP_XOR1>(v);
+  if (N >= 4) v += fg_dpp<FG_DPP_XOR2>(v);
+  if (N >= 8) v += fg_dpp<FG_DPP_HALF_MIRROR>(v);
+  if (N >= 16) v += fg_dpp<FG_DPP_MIRROR>(v);
+  if (N >= 32) v += __shfl_xor(v, 16, 64);
+  if (N >= 64) v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+// Maximum over the 64 lanes of the wave, as a wave-uniform value.
+__device__ __forceinline__ float fg_wave_max(float v) {
+  v = fmaxf(v, fg_dpp<FG_DPP_XOR1>(v));
+  v = fmaxf(v, fg_dpp<FG_DPP_XOR2>(v));
+  v = fmaxf(v, fg_dpp<FG_DPP_HALF_MIRROR>(v));
+  v = fmaxf(v, fg_dpp<FG_DPP_MIRROR>(v));
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
 // Deterministic block-wide sums (fixed tree order). `red` is LDS scratch with one slot per
 // wave; every thread of the block must call. All threads receive the total.
 __device__ __forceinline__ double fg_block_sum_f64(double v, double* red) {

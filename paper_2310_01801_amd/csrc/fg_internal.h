@@ -35,7 +35,7 @@ struct fg_layout {
   size_t clogit;    // [pool, G] float   this step's scaled logit of every held token, per query head
   // decode scratch
   size_t chunk_off; // [U + 1] int32  first chunk of each unit in the flat work list
-  size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, 1, pool offset lo/hi, 0, 0
+  size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, tokens held, pool offset lo/hi, 0, 0
   size_t part;      // [max_chunks, G, d + 2] float  split-KV partial (max, sum, o) per query head
   size_t total;
   int64_t pool_tokens;
@@ -93,7 +93,7 @@ struct fg_decode_args {
   const void* q; const void* k_new; const void* v_new; const uint8_t* class_new; void* out;
   const int32_t* policy; const int32_t* cap; const int64_t* off; int32_t* len; int32_t* flags;
   void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; float* clogit;
-  const int32_t* chunk_off; const int32_t* item_unit; float* part;
+  const int32_t* chunk_off; int32_t* item_unit; float* part;
   int U, n, d, dtype, units_per_seq, w, step, G;
   int family[4];   // FG_COMP_* mask of policy ids 0..3 (stability probe)
   double* probe;   // NULL, or [U, 5]: this step's attention mass on every family member
@@ -115,7 +115,7 @@ hipError_t fg_launch_profile_f32(const fg_profile_args&, int pass, hipStream_t);
 hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t);
 hipError_t fg_launch_select(const fg_select_args&, hipStream_t);
 hipError_t fg_launch_compact(const fg_compact_args&, hipStream_t);
-hipError_t fg_launch_offsets(const int32_t* cap, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
+hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
                              int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
                              hipStream_t);
 hipError_t fg_launch_decode_attn(const fg_decode_args&, hipStream_t);

@@ -171,10 +171,12 @@ __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restr
 }
 
 // Work-item records of the decode attention kernel: item c of unit u covers slots
-// [256 * (c - chunk_off[u]), +256) of that unit. 8 ints per item: unit, chunk, cap, 1, off lo, off hi, 0, 0.
+// [256 * (c - chunk_off[u]), +256) of that unit. 8 ints per item: unit, chunk, cap, tokens held
+// by the unit (kept current by the update kernel), off lo, off hi, 0, 0.
 __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restrict__ chunk_off,
                                                           const int32_t* __restrict__ cap,
                                                           const int64_t* __restrict__ off,
+                                                          const int32_t* __restrict__ len,
                                                           int32_t* __restrict__ item_rec,
                                                           const int32_t* __restrict__ flags, int U) {
   if (flags[0] != 0) return;
@@ -184,7 +186,7 @@ __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restr
   const int c0 = chunk_off[u], c1 = chunk_off[u + 1];
   for (int c = c0; c < c1; ++c) {
     int32_t* r = item_rec + (size_t)c * 8;
-    r[0] = u; r[1] = c - c0; r[2] = cap[u]; r[3] = 1;
+    r[0] = u; r[1] = c - c0; r[2] = cap[u]; r[3] = len[u];
     r[4] = (int32_t)(o & 0xffffffffll); r[5] = (int32_t)(o >> 32); r[6] = 0; r[7] = 0;
   }
 }
@@ -313,13 +315,13 @@ hipError_t fg_launch_compact(const fg_compact_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t fg_launch_offsets(const int32_t* cap, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
-                             int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
+hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, int64_t* off, int32_t* chunk_off,
+                             int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
                              hipStream_t s) {
   hipLaunchKernelGGL(fg_offsets_kernel, dim3(1), dim3(1024), 0, s, cap, off, chunk_off, flags, U,
                      pool_tokens, max_chunks);
   hipLaunchKernelGGL(fg_item_map_kernel, dim3((unsigned)((U + 255) / 256)), dim3(256), 0, s,
-                     chunk_off, cap, off, item_unit, flags, U);
+                     chunk_off, cap, off, len, item_unit, flags, U);
   return hipGetLastError();
 }
 
