@@ -263,7 +263,7 @@ __device__ __forceinline__ void fg_store_out<4>(void* out, size_t idx, float v) 
 }
 
 template <int ESIZE, int D, bool GRP>
-__global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a) {
+__global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args a) {
   constexpr int RB = D * ESIZE, CPR = RB / 16;
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
@@ -297,13 +297,21 @@ __global__ __launch_bounds__(256) void fg_decode_finish_kernel(fg_decode_args a)
   for (int h = 0; h < G; ++h) {
     const float* ph = part + (size_t)h * (D + 2);
     const size_t cs = (size_t)G * (D + 2);  // stride between chunks
-    float Mh = FG_NEG_BIG;
-    for (int cix = 0; cix < nch; ++cix) Mh = fmaxf(Mh, ph[cix * cs]);
-    float Lsum = 0.f;
-    for (int cix = 0; cix < nch; ++cix) Lsum += ph[cix * cs + 1] * fg_exp2(ph[cix * cs] - Mh);
+    // (max, sum) of the chunks: every wave does it for itself, one chunk per lane, so the loads
+    // of all chunks are in flight together and no workgroup barrier is needed
+    const int lane = tid & 63;
+    float mc = FG_NEG_BIG, lc = 0.f;     // first chunk of this lane
+    if (lane < nch) { mc = ph[lane * cs]; lc = ph[lane * cs + 1]; }
+    float Mh = mc;
+    for (int cix = lane + 64; cix < nch; cix += 64) Mh = fmaxf(Mh, ph[cix * cs]);
+    Mh = fg_wave_max(Mh);
+    float Lsum = lc * fg_exp2(mc - Mh);
+    for (int cix = lane + 64; cix < nch; cix += 64) Lsum += ph[cix * cs + 1] * fg_exp2(ph[cix * cs] - Mh);
+    Lsum = fg_group_sum<64>(Lsum);
     const float invh = 1.0f / Lsum;
     if (tid < D) {
       float o = 0.f;
+#pragma unroll 4
       for (int cix = 0; cix < nch; ++cix) o += ph[cix * cs + 2 + tid] * fg_exp2(ph[cix * cs] - Mh);
       fg_store_out<ESIZE>(a.out, ((size_t)u * G + h) * D + tid, o * invh);
     }

@@ -72,11 +72,73 @@ __device__ __forceinline__ float fg_wave_max(float v) {
   return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
 }
 
+template <int CTRL>
+__device__ __forceinline__ int fg_dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);  // lanes without a source read 0
+}
+__device__ __forceinline__ int fg_readlane_i32(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+
+// Sum over the 64 lanes of the wave, as a wave-uniform value (fixed order).
+__device__ __forceinline__ int fg_wave_sum_i32(int v) {
+  v += fg_dpp_i32<FG_DPP_XOR1>(v);
+  v += fg_dpp_i32<FG_DPP_XOR2>(v);
+  v += fg_dpp_i32<FG_DPP_HALF_MIRROR>(v);
+  v += fg_dpp_i32<FG_DPP_MIRROR>(v);
+  return (fg_readlane_i32(v, 0) + fg_readlane_i32(v, 16)) + (fg_readlane_i32(v, 32) + fg_readlane_i32(v, 48));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double fg_dpp_f64(double v) {
+  return __hiloint2double(fg_dpp_i32<CTRL>(__double2hiint(v)), fg_dpp_i32<CTRL>(__double2loint(v)));
+}
+__device__ __forceinline__ double fg_wave_sum_f64(double v) {
+  v += fg_dpp_f64<FG_DPP_XOR1>(v);
+  v += fg_dpp_f64<FG_DPP_XOR2>(v);
+  v += fg_dpp_f64<FG_DPP_HALF_MIRROR>(v);
+  v += fg_dpp_f64<FG_DPP_MIRROR>(v);
+  const int hi = __double2hiint(v), lo = __double2loint(v);
+  const double r0 = __hiloint2double(fg_readlane_i32(hi, 0), fg_readlane_i32(lo, 0));
+  const double r1 = __hiloint2double(fg_readlane_i32(hi, 16), fg_readlane_i32(lo, 16));
+  const double r2 = __hiloint2double(fg_readlane_i32(hi, 32), fg_readlane_i32(lo, 32));
+  const double r3 = __hiloint2double(fg_readlane_i32(hi, 48), fg_readlane_i32(lo, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+// Bitwise OR / AND of a 64-bit value over the wave (wave-uniform results).
+__device__ __forceinline__ void fg_wave_or_and_u64(unsigned long long v_or, unsigned long long v_and,
+                                                   unsigned long long* out_or, unsigned long long* out_and) {
+  int olo = (int)(unsigned)v_or, ohi = (int)(unsigned)(v_or >> 32);
+  int alo = (int)(unsigned)v_and, ahi = (int)(unsigned)(v_and >> 32);
+#define FG_STEP(CTRL)                                                            \
+  olo |= fg_dpp_i32<CTRL>(olo); ohi |= fg_dpp_i32<CTRL>(ohi);                    \
+  alo &= fg_dpp_i32<CTRL>(alo); ahi &= fg_dpp_i32<CTRL>(ahi);
+  FG_STEP(FG_DPP_XOR1) FG_STEP(FG_DPP_XOR2) FG_STEP(FG_DPP_HALF_MIRROR) FG_STEP(FG_DPP_MIRROR)
+#undef FG_STEP
+  unsigned ro_lo = 0, ro_hi = 0, ra_lo = ~0u, ra_hi = ~0u;
+#pragma unroll
+  for (int r = 0; r < 64; r += 16) {
+    ro_lo |= (unsigned)fg_readlane_i32(olo, r); ro_hi |= (unsigned)fg_readlane_i32(ohi, r);
+    ra_lo &= (unsigned)fg_readlane_i32(alo, r); ra_hi &= (unsigned)fg_readlane_i32(ahi, r);
+  }
+  *out_or = ((unsigned long long)ro_hi << 32) | ro_lo;
+  *out_and = ((unsigned long long)ra_hi << 32) | ra_lo;
+}
+
+// Inclusive prefix sum over the 64 lanes of the wave.
+__device__ __forceinline__ int fg_wave_incscan_i32(int v) {
+  v += fg_dpp_i32<0x111>(v);  // row_shr:1
+  v += fg_dpp_i32<0x112>(v);  // row_shr:2
+  v += fg_dpp_i32<0x114>(v);  // row_shr:4
+  v += fg_dpp_i32<0x118>(v);  // row_shr:8   -> inclusive within each row of 16
+  const int t0 = fg_readlane_i32(v, 15), t1 = fg_readlane_i32(v, 31), t2 = fg_readlane_i32(v, 47);
+  const int row = (threadIdx.x & 63) >> 4;
+  return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+}
+
 // Deterministic block-wide sums (fixed tree order). `red` is LDS scratch with one slot per
 // wave; every thread of the block must call. All threads receive the total.
 __device__ __forceinline__ double fg_block_sum_f64(double v, double* red) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += fg_shfl_xor_f64(v, m);
+  v = fg_wave_sum_f64(v);
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[wave] = v;
@@ -87,8 +149,7 @@ __device__ __forceinline__ double fg_block_sum_f64(double v, double* red) {
 }
 
 __device__ __forceinline__ int fg_block_sum_i32(int v, int* red) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+  v = fg_wave_sum_i32(v);
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[wave] = v;
@@ -102,12 +163,7 @@ __device__ __forceinline__ int fg_block_sum_i32(int v, int* red) {
 // 64). `red` needs 17 ints. Returns the exclusive prefix; *total receives the block sum.
 __device__ __forceinline__ int fg_block_exscan_i32(int v, int* red, int* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  int inc = v;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int t = __shfl_up(inc, o, 64);
-    if (lane >= o) inc += t;
-  }
+  const int inc = fg_wave_incscan_i32(v);
   __syncthreads();
   if (lane == 63) red[wave] = inc;
   __syncthreads();

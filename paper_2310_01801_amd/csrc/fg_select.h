@@ -37,7 +37,7 @@ __device__ __forceinline__ void fg_hist_add(int* hist, bool active, int digit) {
   const unsigned long long act = __ballot(active);
   if (act == 0ull) return;
   const int leader = __ffsll((long long)act) - 1;
-  const int d0 = __shfl(digit, leader, 64);
+  const int d0 = __builtin_amdgcn_readlane(digit, leader);  // `leader` is wave-uniform
   const bool same = active && digit == d0;
   const unsigned long long grp = __ballot(same);
   if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[d0], (int)__popcll(grp));
@@ -86,10 +86,11 @@ __device__ __forceinline__ fg_topk fg_select_topk_impl(const uint64_t (&kc)[NC >
       k_and &= key;
     }
   }
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) {
-    k_or |= ((uint64_t)__shfl_xor((int)(k_or >> 32), o, 64) << 32) | (uint32_t)__shfl_xor((int)k_or, o, 64);
-    k_and &= ((uint64_t)__shfl_xor((int)(k_and >> 32), o, 64) << 32) | (uint32_t)__shfl_xor((int)k_and, o, 64);
+  {
+    unsigned long long wo, wa;
+    fg_wave_or_and_u64(k_or, k_and, &wo, &wa);
+    k_or = wo;
+    k_and = wa;
   }
   __syncthreads();
   if (lane == 0) { sm->w_or[wave] = k_or; sm->w_and[wave] = k_and; }
