@@ -6,12 +6,14 @@
 //       of its held slots with 16-byte-per-lane coalesced loads (a 256-byte bf16 row = 16
 //       lanes, 4 rows per wave load), keeps the scaled logits, and emits (max, sum, o) of its
 //       chunk. The item that owns the first free slot takes the new token from k_new/v_new
-//       and appends it to the cache on the way.
+//       and appends it to the cache on the way. With grouped query heads the rows loaded by
+//       an item serve every head of the unit (one partial per head).
 //   fg_decode_finish_kernel   one workgroup per unit: merges the chunk partials into the
 //       attention output; adds this step's attention to the cumulative scores (policies with
-//       `frequent`); re-derives the kept set  special | punct | TopK(score, k_f(L)) | window
-//       and releases the evicted slots in place (holes below the new length are filled with
-//       the kept rows from above it).
+//       `frequent`, or every policy when the step is probed); re-derives the kept set from the
+//       policy's components  special | punct | TopK(score, k_f(L)) | window  and releases the
+//       evicted slots in place (holes below the new length are filled with the kept rows from
+//       above it); optionally reports the step's attention mass on every policy's tokens.
 #include "fg_common.h"
 #include "fg_internal.h"
 #include "fg_select.h"
