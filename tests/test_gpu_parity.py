@@ -281,3 +281,30 @@ def test_runs_on_a_side_stream():
         rep = H.compare(run, probe_steps=[3])
     side.synchronize()
     _report("side stream", rep)
+
+
+def _random_case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    families = [None, (8, 12, 13, 15), (1, 5, 13, 0), (2, 4, 8, 1), (4, 8, 12, 0)]
+    return dict(
+        n=int(rng.choice([1, 2, 7, 31, 32, 33, 63, 64, 65, 100, 129, 255, 256, 257, 300])),
+        S=int(rng.choice([0, 1, 3, 17, 40, 70])),
+        d=int(rng.choice([64, 128])), dtype=str(rng.choice(["bf16", "f32"])),
+        T=float(rng.choice([0.5, 0.8, 0.9, 0.95, 0.99, 1.0])),
+        r_l=float(rng.choice([0.0, 0.05, 0.3, 0.7, 1.0])), r_f=float(rng.choice([0.0, 0.05, 0.3, 0.7, 1.0])),
+        heads=int(rng.integers(1, 8)), batch=int(rng.integers(1, 4)), G=int(rng.choice([1, 1, 2, 3])),
+        family=families[int(rng.integers(0, len(families)))], forced=int(rng.choice([-1, -1, -1, 4])))
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_small_configurations(seed):
+    """Seeded sweep over shapes, dtypes, budgets, thresholds, policy tables and group sizes, every
+    unit and every step against the oracle: the cases nobody thought of one by one."""
+    c = _random_case(seed)
+    w = W["llama7b_b1"].scaled(name=f"rand{seed}", layers=1, heads=c["heads"], batch=c["batch"], prompt_len=c["n"],
+                               steps=c["S"], head_dim=c["d"], dtype=c["dtype"], T=c["T"], r_l=c["r_l"], r_f=c["r_f"],
+                               seed=2000 + seed)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=c["forced"], family=c["family"], group_size=c["G"])
+    probe = [s for s in (0, c["S"] // 2) if s < c["S"]]
+    rep = H.compare(run, probe_steps=probe)
+    _report(f"random {seed} {c}", rep)
