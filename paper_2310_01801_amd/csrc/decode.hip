@@ -21,6 +21,7 @@
 namespace {
 
 constexpr int CH = FG_DECODE_CHUNK;
+constexpr int FG_MOVE_LDS = 64;  // released slots per step whose move lists stay in shared memory
 
 template <int ESIZE>
 __device__ __forceinline__ void fg_unpack(const u32x4& v, float* f);
@@ -392,8 +393,12 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
     if (scored) {
       const int k_f = fg_budget(a.r_f, p_new + 1);
       __syncthreads();  // score[] is re-read by other threads only if the boundary value is tied
-      tk = fg_select_topk_regs<NC>(kc, [&](int j) { return score[j]; },
-                                   [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
+      // without the probe only the unprotected tokens' membership matters: try the lowest ones
+      bool done = false;
+      if (!probing && k_f > 0 && k_f < L && L <= 0xffff) done = fg_evict_cut_regs<NC>(kc, prot, L, k_f, dred, ired, &tk);
+      if (!done)
+        tk = fg_select_topk_regs<NC>(kc, [&](int j) { return score[j]; },
+                                     [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
     }
   } else if (scored) {
     for (int j = tid; j < L; j += 256) {
@@ -466,6 +471,8 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
 
   // ---- in-place release: i-th hole (evicted slot below new_len) <- i-th kept slot above it
   int* scratch = reinterpret_cast<int*>(a.clogit + off * G);  // logits are dead from here on
+  __shared__ int s_move[2 * FG_MOVE_LDS];
+  bool in_lds = false;
   __syncthreads();
   int run_h = 0, run_m = 0;
   if (small) {
@@ -480,21 +487,25 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
         nm += (j >= new_len && k) ? 1 : 0;
       }
     }
-    int tot_h, tot_m;
-    int at_h = fg_block_exscan_i32(nh, ired, &tot_h);
-    __syncthreads();
-    int at_m = fg_block_exscan_i32(nm, ired, &tot_m);
+    // one scan for both counts (each below 2^16: L <= 256 * NC)
+    int tot;
+    const int at = fg_block_exscan_i32(nh | (nm << 16), ired, &tot);
+    int at_h = at & 0xffff, at_m = at >> 16;
+    run_h = tot & 0xffff;
+    run_m = tot >> 16;
+    // a step releases very few slots: the two lists then stay in shared memory
+    in_lds = run_h <= FG_MOVE_LDS;
+    int* holes = in_lds ? s_move : scratch;
+    int* movers_end = in_lds ? s_move + 2 * FG_MOVE_LDS - 1 : scratch + cap - 1;  // filled downwards
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
       const int j = tid + 256 * i;
       if (j < L) {
         const bool k = (keepbits >> i) & 1u;
-        if (j < new_len && !k) scratch[at_h++] = j;
-        if (j >= new_len && k) scratch[cap - 1 - (at_m++)] = j;
+        if (j < new_len && !k) holes[at_h++] = j;
+        if (j >= new_len && k) *(movers_end - (at_m++)) = j;
       }
     }
-    run_h = tot_h;
-    run_m = tot_m;
     __syncthreads();
   } else {
     for (int base = 0; base < L; base += 256) {
@@ -539,7 +550,8 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
     // rows and bookkeeping in one sweep: CPR lanes copy the row, one more moves score/pos/class
     for (int q = tid; q < moves * (CPR + 1); q += 256) {
       const int i = q / (CPR + 1), ch = q % (CPR + 1);
-      const int dst = scratch[i], src = scratch[cap - 1 - i];
+      const int dst = in_lds ? s_move[i] : scratch[i];
+      const int src = in_lds ? s_move[2 * FG_MOVE_LDS - 1 - i] : scratch[cap - 1 - i];
       if (ch < CPR) {
         const u32x4 kr = *reinterpret_cast<const u32x4*>(ck + (size_t)src * RB + ch * 16);
         const u32x4 vr = *reinterpret_cast<const u32x4*>(cv + (size_t)src * RB + ch * 16);

@@ -104,6 +104,20 @@ __device__ __forceinline__ double fg_wave_sum_f64(double v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// Minimum of a double over the wave, wave-uniform (inputs must not be NaN).
+__device__ __forceinline__ double fg_wave_min_f64(double v) {
+  v = fmin(v, fg_dpp_f64<FG_DPP_XOR1>(v));
+  v = fmin(v, fg_dpp_f64<FG_DPP_XOR2>(v));
+  v = fmin(v, fg_dpp_f64<FG_DPP_HALF_MIRROR>(v));
+  v = fmin(v, fg_dpp_f64<FG_DPP_MIRROR>(v));
+  const int hi = __double2hiint(v), lo = __double2loint(v);
+  const double r0 = __hiloint2double(fg_readlane_i32(hi, 0), fg_readlane_i32(lo, 0));
+  const double r1 = __hiloint2double(fg_readlane_i32(hi, 16), fg_readlane_i32(lo, 16));
+  const double r2 = __hiloint2double(fg_readlane_i32(hi, 32), fg_readlane_i32(lo, 32));
+  const double r3 = __hiloint2double(fg_readlane_i32(hi, 48), fg_readlane_i32(lo, 48));
+  return fmin(fmin(r0, r1), fmin(r2, r3));
+}
+
 // Bitwise OR / AND of a 64-bit value over the wave (wave-uniform results).
 __device__ __forceinline__ void fg_wave_or_and_u64(unsigned long long v_or, unsigned long long v_and,
                                                    unsigned long long* out_or, unsigned long long* out_and) {

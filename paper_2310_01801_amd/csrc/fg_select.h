@@ -171,6 +171,57 @@ __device__ __forceinline__ fg_topk fg_select_topk_regs(const uint64_t (&kc)[NC],
   return fg_select_topk_impl<NC>(kc, score, pos, m, k, sm);
 }
 
+// Shortcut for the per-step kept-set update. Only tokens that nothing else protects (`prot`
+// bit clear) can leave, and they leave lowest score first: a token is outside the top k exactly
+// if at least k scores are larger. So instead of locating the k-th largest score, test the
+// lowest unprotected score, then the next one, ... until one stays (a step evicts very few
+// tokens). Returns false when the shortcut does not apply -- two equal scores at a tested value,
+// or more than FG_EVICT_TRIES evictions -- and the caller runs the full selection instead.
+// On success every unprotected token with key >= out->thr is in the top k (mode 2, no position
+// tie-break needed). Keys of slot tid + 256 i are kc[i] (valid while < m). 256 threads.
+#define FG_EVICT_TRIES 6
+template <int NC>
+__device__ __forceinline__ bool fg_evict_cut_regs(const uint64_t (&kc)[NC], uint32_t prot, int m, int k,
+                                                  double* red_d, int* red_i, fg_topk* out) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const double inf = __longlong_as_double(0x7ff0000000000000ll);
+  double last = -1.0;  // every evicted score so far is <= last
+  for (int it = 0; it < FG_EVICT_TRIES; ++it) {
+    double loc = inf;
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      const double v = __longlong_as_double((long long)kc[i]);
+      if (j < m && !((prot >> i) & 1u) && v > last) loc = fmin(loc, v);
+    }
+    loc = fg_wave_min_f64(loc);
+    __syncthreads();
+    if (lane == 0) red_d[wave] = loc;
+    __syncthreads();
+    const double kmin = fmin(fmin(red_d[0], red_d[1]), fmin(red_d[2], red_d[3]));
+    out->mode = 2; out->pthr = 0xffffffffu;
+    if (kmin == inf) {  // no unprotected token is left: none of them is in the top k
+      out->thr = 0x7ff0000000000000ull;
+      return true;
+    }
+    int cnt = 0;  // scores above kmin in the low half, scores equal to it in the high half
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+      const int j = tid + 256 * i;
+      const double v = __longlong_as_double((long long)kc[i]);
+      if (j < m) cnt += (v > kmin ? 1 : 0) + (v == kmin ? (1 << 16) : 0);
+    }
+    const int tot = fg_block_sum_i32(cnt, red_i);
+    if ((tot >> 16) != 1) return false;       // a tie at the tested value: needs the position rule
+    if ((tot & 0xffff) < k) {                  // fewer than k larger scores: it stays, and so do all above it
+      out->thr = (uint64_t)__double_as_longlong(kmin);
+      return true;
+    }
+    last = kmin;                               // at least k larger scores: it leaves; test the next one
+  }
+  return false;
+}
+
 // ScoreFn(j) -> double (>= 0), PosFn(j) -> uint32 position (unique per element).
 template <class ScoreFn, class PosFn>
 __device__ __forceinline__ fg_topk fg_select_topk(ScoreFn score, PosFn pos, int m, int k,
