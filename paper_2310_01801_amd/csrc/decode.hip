@@ -14,6 +14,8 @@
 //       policy's components  special | punct | TopK(score, k_f(L)) | window  and releases the
 //       evicted slots in place (holes below the new length are filled with the kept rows from
 //       above it); optionally reports the step's attention mass on every policy's tokens.
+#include <type_traits>
+
 #include "fg_common.h"
 #include "fg_internal.h"
 #include "fg_select.h"
@@ -266,7 +268,7 @@ __device__ __forceinline__ void fg_store_out<4>(void* out, size_t idx, float v) 
 }
 
 template <int ESIZE, int D, bool GRP>
-__global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args a) {
+__global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_decode_args a) {
   constexpr int RB = D * ESIZE, CPR = RB / 16;
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
@@ -349,7 +351,10 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
 
   // Fast path (L <= 256 * NC): each thread keeps its slots' updated scores and a "protected"
   // bit (special / punctuation / window) in registers, so every later phase is register-only.
-  constexpr int NC = 24;
+  // The code below is straight-line per slot, i.e. executed once per workgroup and bound by
+  // instruction fetch: it is instantiated for a few sizes and the smallest one that fits is taken.
+  auto update = [&](auto nc_tag) __attribute__((always_inline)) {
+  constexpr int NC = decltype(nc_tag)::value;
   uint64_t kc[NC];
   uint32_t prot = 0;
   const bool small = L <= 256 * NC;
@@ -568,6 +573,11 @@ __global__ __launch_bounds__(256, 4) void fg_decode_finish_kernel(fg_decode_args
     }
   }
   set_len(new_len);
+  };
+  if (L <= 256 * 2) update(std::integral_constant<int, 2>{});
+  else if (L <= 256 * 4) update(std::integral_constant<int, 4>{});
+  else if (L <= 256 * 8) update(std::integral_constant<int, 8>{});
+  else update(std::integral_constant<int, 24>{});
 }
 
 }  // namespace
