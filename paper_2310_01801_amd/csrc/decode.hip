@@ -95,30 +95,41 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
       *reinterpret_cast<u32x4*>(&s_q[i * 16]) = *reinterpret_cast<const u32x4*>(qu + (size_t)i * 16);
   }
 
+  // All row loads are issued back to back with no control flow in between (a branch per row
+  // makes the compiler wait for each pair of loads before it issues the next). Raw buffer
+  // loads over the chunk's cached rows: one per-lane offset, a constant offset per load, and
+  // rows past the end read as zeros. The new token is not in the cache yet: its lane group
+  // takes it from the step inputs afterwards and appends it.
   u32x4 kv[ITERS], vv[ITERS];
+  const int ncached = min(cnt, Lold - start);  // rows of this chunk that are in the cache
+  const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(ck) + (off + start) * RB, 0, ncached * RB, 0x00020000);
+  const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char*>(cv) + (off + start) * RB, 0, ncached * RB, 0x00020000);
+  const int voff = (wave * TPW + sub) * RB + g * 16;
 #pragma unroll
   for (int it = 0; it < ITERS; ++it) {
-    const int tok = wave * TPW + it * TPL + sub;
-    const int slot = start + tok;
-    u32x4 kk = {0u, 0u, 0u, 0u}, vw = {0u, 0u, 0u, 0u};
-    if (tok < cnt) {
-      if (slot == Lold) {  // the new token: read it from the step inputs and append it
-        kk = *reinterpret_cast<const u32x4*>(kn + g * 16);
-        vw = *reinterpret_cast<const u32x4*>(vn + g * 16);
-        *reinterpret_cast<u32x4*>(static_cast<char*>(a.ck) + (off + slot) * RB + g * 16) = kk;
-        *reinterpret_cast<u32x4*>(static_cast<char*>(a.cv) + (off + slot) * RB + g * 16) = vw;
+    kv[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(k_rsrc, voff, it * TPL * RB, 0));
+    vv[it] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(v_rsrc, voff, it * TPL * RB, 0));
+  }
+  if (Lold >= start && Lold < start + CH) {  // this item owns the first free slot
+    const u32x4 knew = *reinterpret_cast<const u32x4*>(kn + g * 16);
+    const u32x4 vnew = *reinterpret_cast<const u32x4*>(vn + g * 16);
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+      const int slot = start + wave * TPW + it * TPL + sub;
+      if (slot == Lold) {
+        kv[it] = knew;
+        vv[it] = vnew;
+        *reinterpret_cast<u32x4*>(static_cast<char*>(a.ck) + (off + slot) * RB + g * 16) = knew;
+        *reinterpret_cast<u32x4*>(static_cast<char*>(a.cv) + (off + slot) * RB + g * 16) = vnew;
         if (g == 0) {
           a.cpos[off + slot] = a.n + a.step;
           a.ccls[off + slot] = a.class_new[u / a.units_per_seq];
           a.cscore[off + slot] = 0.0;
         }
-      } else {
-        kk = *reinterpret_cast<const u32x4*>(ck + (off + slot) * RB + g * 16);
-        vw = *reinterpret_cast<const u32x4*>(cv + (off + slot) * RB + g * 16);
       }
     }
-    kv[it] = kk;
-    vv[it] = vw;
   }
 
   if (GRP) {
