@@ -186,6 +186,12 @@ def main():
                            full_cache_tokens_per_unit=n + (S + 1) / 2)
     pol_hist = np.bincount(runs[0]["policy"].cpu().numpy(), minlength=5).tolist()
 
+    # ---- what library kernels reach on this machine, next to the published peaks (context only)
+    ref = reference_rates(dev)
+    roof_profile["box_reference"] = {"bf16_gemm_8192_TFLOPs": ref["gemm_tflops"]}
+    if roof_decode:
+        roof_decode["box_reference"] = {"device_copy_1GiB_GBps_read_plus_write": ref["copy_gbps"]}
+
     dominant = roof_decode if (roof_decode and phase["decode_attn"] > sweeps_ms) else roof_profile
 
     # ---- CPU oracle on a bounded sample (never tuned; reported, not a target)
@@ -213,6 +219,35 @@ def main():
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
+
+
+def reference_rates(dev):
+    """A large bf16 GEMM (hipBLASLt through torch) and a 1 GiB device copy, timed with events:
+    the practical ceilings of this machine for matrix-core and HBM bound work."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    a = torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16)
+    b = torch.randn((8192, 8192), device=dev, dtype=torch.bfloat16)
+    for _ in range(3):
+        torch.matmul(a, b)
+    ev[0].record()
+    for _ in range(10):
+        torch.matmul(a, b)
+    ev[1].record()
+    torch.cuda.synchronize()
+    gemm = 10 * 2 * 8192.0 ** 3 / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12
+    del a, b
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev[0].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev[1].record()
+    torch.cuda.synchronize()
+    copy = 5 * 2 * float(1 << 30) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+    del src, dst
+    return dict(gemm_tflops=gemm, copy_gbps=copy)
 
 
 def cpu_baseline(w, plan, cls_p, cls_d, sample_units):
