@@ -129,8 +129,9 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   float m_run[2] = {FG_NEG_BIG, FG_NEG_BIG}, l_run[2] = {0.f, 0.f};  // pass 1
   double col_acc[2] = {0.0, 0.0}, band_acc[2] = {0.0, 0.0};          // pass 2
 
-  // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards, so that the
-  // workgroups of one unit stream the same tiles at the same time, measured 25 % slower).
+  // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards from the end,
+  // in lockstep or skewed by a few tiles per block so that the blocks of a unit share the
+  // streamed tiles in L2, measured the same time).
   const int nt = t_end - t_begin;     // tiles per head
   const int n_it = nt * heads;
   if (n_it > 0) {
