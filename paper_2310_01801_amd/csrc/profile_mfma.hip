@@ -47,9 +47,16 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   // ---- which (unit, owner block): units of one XCD walk one unit's blocks back to back
   const int idx = blockIdx.x;
   const int xcd = idx & 7, rest = idx >> 3;
-  const int blk_ord = rest % nblk;
-  const int unit = (rest / nblk) * 8 + xcd;
+  const int npair = (nblk + 1) / 2;
+  const int pair_ord = rest % npair;
+  const int unit = (rest / npair) * 8 + xcd;
   if (unit >= U) return;
+  // A workgroup takes two owner blocks of the unit, the pair_ord-th heaviest and the
+  // pair_ord-th lightest one: every workgroup of a unit then has the same amount of work and
+  // the start-up of a workgroup is paid once per pair.
+  for (int half = 0; half < 2; ++half) {
+  const int blk_ord = half == 0 ? pair_ord : nblk - 1 - pair_ord;
+  if (half == 1 && blk_ord == pair_ord) break;  // the middle block of an odd count is alone
   const int blk = (PASS == 1) ? (nblk - 1 - blk_ord) : blk_ord;  // heaviest first
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -285,6 +292,8 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
       }
     }
   }
+  __syncthreads();  // the tile buffers are reused by the second block
+  }
 }
 
 template <int D>
@@ -292,7 +301,7 @@ hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const int nblk = (a.n + kOwnPerBlock - 1) / kOwnPerBlock;
   const int units = (pass == 1) ? a.U * a.G : a.U;  // sweep 1: one unit per query head
   const int ugroups = (units + 7) / 8;
-  const dim3 grid((unsigned)(8 * nblk * ugroups)), block(256);
+  const dim3 grid((unsigned)(8 * ((nblk + 1) / 2) * ugroups)), block(256);
   const float c = a.scale * FG_LOG2E;
   const __bf16* Q = static_cast<const __bf16*>(a.Q);
   const __bf16* K = static_cast<const __bf16*>(a.K);
