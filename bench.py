@@ -27,8 +27,8 @@ PEAK_HBM = 8.0e12         # B/s
 # profiles/hbm_traffic_llama7b_b1_pmc.md for the commands. Offline numbers: the counters cannot
 # be read inside a timed run.
 MEASURED_TRAFFIC = {
-    "llama7b_b1": {"sweeps": 1399e6 + 8.4e6 + 2209e6 + 33.6e6,   # both sweeps together
-                   "decode_attn": 540e6 + 7.8e6},                # first 16 decode steps, per launch
+    "llama7b_b1": {"sweeps": 1391e6 + 8.4e6 + 2278e6 + 33.6e6,   # both sweeps together
+                   "decode_attn": 540e6 + 7.7e6},                # first 16 decode steps, per launch
 }
 
 
