@@ -132,12 +132,13 @@ def test_call_order_and_capacity_errors():
 def test_llama7b_full_size_sampled_units():
     """BASELINE config 2 at full size (1024 units, n = 2048) in the launch configuration the
     benchmark times; the oracle checks a seeded sample of units one by one."""
-    w = W["llama7b_b1"].scaled(steps=24)
+    w = W["llama7b_b1"]            # the full decode horizon of the benchmark: 256 steps
     run = H.GpuRun(w, range(w.num_units))
     rng = np.random.default_rng(5)
-    sample = sorted(rng.choice(w.num_units, size=12, replace=False).tolist())
-    rep = H.compare(run, check_units=sample, state_steps=[0, 11, 23], check_rows=False, probe_steps=[10, 20])
-    _report("llama7b_b1 full size, 12 sampled units", rep)
+    sample = sorted(rng.choice(w.num_units, size=16, replace=False).tolist())
+    rep = H.compare(run, check_units=sample, state_steps=list(range(0, 256, 17)) + [255], check_rows=False,
+                    probe_steps=[100, 200])
+    _report("llama7b_b1 full size, 16 sampled units, 256 steps", rep)
 
 
 # ---- the remaining BASELINE configurations at full size, oracle on a seeded sample of units.
