@@ -141,9 +141,8 @@ def test_llama7b_full_size_sampled_units():
     _report("llama7b_b1 full size, 16 sampled units, 256 steps", rep)
 
 
-# ---- the remaining BASELINE configurations at full size, oracle on a seeded sample of units.
-# The decode horizon is shortened (the step logic is covered above; these runs are about the
-# shapes, the ragged-length mix and the grid sizes of the large launches).
+# ---- the remaining BASELINE configurations at full size and over their whole decode horizon,
+# oracle on a seeded sample of units.
 
 def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0, probe_steps=()):
     w = W[name].scaled(steps=steps) if T is None else W[name].scaled(steps=steps, T=T)
@@ -158,16 +157,16 @@ def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0, probe_st
 
 @pytest.mark.parametrize("T", [0.90, 0.98])
 def test_llama7b_b16_full_size_sampled_units(T):
-    _full_size("llama7b_b16", 12, 12, T=T, seed=16)
+    _full_size("llama7b_b16", 12, 512, T=T, seed=16, state_steps=[0, 1, 63, 255, 511])
 
 
 def test_llama13b_b4_full_size_sampled_units():
-    _full_size("llama13b_b4", 6, 8, seed=13)
+    _full_size("llama13b_b4", 6, 512, seed=13, state_steps=[0, 31, 255, 511])
 
 
 def test_llama65b_b2_full_size_sampled_units():
     # two probed steps: units above 6144 held tokens take the update kernel's large-unit path
-    _full_size("llama65b_b2", 4, 6, seed=65, probe_steps=[1, 4])
+    _full_size("llama65b_b2", 4, 1024, seed=65, probe_steps=[1, 500], state_steps=[0, 15, 511, 1023])
 
 
 @pytest.mark.parametrize("kw", [
