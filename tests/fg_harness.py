@@ -26,6 +26,7 @@ from paper_2310_01801_amd import binding
 MARGIN_EPS = 1e-4
 GAP_EPS = 2e-5          # relative top-k boundary gap below which a unit is "tie-fragile"
 GAP_ABS = 1e-30         # scores this small are below float32's exponent range on the GPU
+TIE_BAND = 1e-4         # tokens swapped at a near-tie lie this close (relative) to the boundary score
 
 
 @dataclasses.dataclass
@@ -34,6 +35,9 @@ class Report:
     margin_excluded: int = 0
     max_probe_err: float = 0.0
     tie_fragile_profile: int = 0
+    tie_swapped_tokens: int = 0
+    tie_agreeing_checks: int = 0
+    tie_diverged_checks: int = 0
     tie_fragile_decode: int = 0
     max_recovery_err: float = 0.0
     max_score_rel_err: float = 0.0
@@ -43,7 +47,7 @@ class Report:
     def line(self) -> str:
         return (f"units={self.units} policies={dict(sorted(self.policies.items()))} "
                 f"margin_excluded={self.margin_excluded} tie_profile={self.tie_fragile_profile} "
-                f"tie_decode={self.tie_fragile_decode} max|dR|={self.max_recovery_err:.2e} "
+                f"tie_decode={self.tie_fragile_decode} tie_swapped={self.tie_swapped_tokens} tie_checks_same/diff={self.tie_agreeing_checks}/{self.tie_diverged_checks} max|dR|={self.max_recovery_err:.2e} "
                 f"max rel|dscore|={self.max_score_rel_err:.2e} max|do|={self.max_out_err:.2e}"
                 + (f" max|dprobe|={self.max_probe_err:.2e}" if self.max_probe_err else ""))
 
@@ -182,7 +186,24 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
         p = ora[i]["profile"]
         gpos, gsc = states[i]
         if i in fragile_from:
+            # near-tie at the top-k boundary: the two kept sets may only differ in tokens whose
+            # column sum lies inside the band around the boundary value, one for one
             assert gpos.size == ora[i]["init_pos"].size
+            only_gpu = np.setdiff1d(gpos, ora[i]["init_pos"])
+            only_ora = np.setdiff1d(ora[i]["init_pos"], gpos)
+            assert only_gpu.size == only_ora.size
+            if only_gpu.size:
+                boundary = np.sort(p.colsum)[::-1][p.k_f - 1]
+                swapped = np.concatenate([only_gpu, only_ora])
+                dev = np.abs(p.colsum[swapped] - boundary) / max(boundary, 1e-300)
+                assert np.all((dev < TIE_BAND) | (p.colsum[swapped] < GAP_ABS)), (i, dev.max())
+                rep.tie_swapped_tokens += int(only_gpu.size)
+            # scores of the common tokens are still compared
+            common = np.intersect1d(gpos, ora[i]["init_pos"])
+            ref = p.colsum[common]
+            got = gsc[np.searchsorted(gpos, common)]
+            rel = np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-6)) if common.size else 0.0
+            assert rel < 5e-5, (i, rel)
             continue
         assert np.array_equal(gpos, ora[i]["init_pos"]), f"unit {run.units[i]}: kept set after compaction differs"
         ref = p.colsum[gpos]
@@ -228,9 +249,15 @@ def compare(run: GpuRun, check_units: Optional[Sequence[int]] = None, steps: Opt
             if st is not None:
                 gpos, gsc = st[i]
                 assert gpos.size == ora[i]["lens"][t], f"unit {run.units[i]} step {t}: length {gpos.size} vs {ora[i]['lens'][t]}"
+                same = np.array_equal(gpos, ora[i]["states"][t])
                 if i in fragile_from and t >= fragile_from[i]:
-                    continue
-                assert np.array_equal(gpos, ora[i]["states"][t]), f"unit {run.units[i]} step {t}: kept set differs"
+                    # after a near-tie the two sides may legitimately hold different tokens; most
+                    # of the time they still agree, which is counted (and then checked in full)
+                    if not same:
+                        rep.tie_diverged_checks += 1
+                        continue
+                    rep.tie_agreeing_checks += 1
+                assert same, f"unit {run.units[i]} step {t}: kept set differs"
                 if _has_frequent(run, ora[i]["profile"].policy) and gpos.size:
                     ref = ora[i]["score_states"][t]
                     rel = float(np.max(np.abs(gsc - ref) / np.maximum(np.abs(ref), 1e-6)))
