@@ -68,7 +68,7 @@ def test_planted_patterns_show_up_in_the_oracle_profile():
         elif pat == synth.LOCAL:
             assert R[3] > R[2] + 0.2                # only the window does
         else:
-            assert R[3] < 0.9                       # broad: nothing short of the full cache
+            assert R[3] < 0.95 and p.policy == 4     # broad: nothing short of the full cache
     assert seen == {synth.LOCAL, synth.SPECIAL, synth.PUNCT, synth.HEAVY, synth.BROAD}
 
 
