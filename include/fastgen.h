@@ -184,6 +184,8 @@ enum {
   FG_PHASE_DECODE_UPDATE = 5, /* merge, score update, evict in place         */
   FG_NUM_PHASES = 6
 };
+/* enable: 0 off; 1 every kernel group; N > 1 the prompt-time phases always and every N-th
+ * decode step (a sample: an event record costs several microseconds on the stream). */
 fg_status fastgen_enable_timing(fastgen_ctx* ctx, int enable);
 /* Waits for the recorded events, then adds up and clears them.
  *   ms        host [FG_NUM_PHASES] double: device milliseconds per phase since the last read.

@@ -145,8 +145,9 @@ class FastGen:
         if st != FG_OK:
             raise FastGenError(st, self.lib.fastgen_last_error(self._ctx).decode())
 
-    def fastgen_enable_timing(self, enable: bool = True) -> None:
-        self._check(self.lib.fastgen_enable_timing(self._ctx, 1 if enable else 0))
+    def fastgen_enable_timing(self, enable=True) -> None:
+        """True/1: time every kernel group; N > 1: the prompt phases and every N-th decode step."""
+        self._check(self.lib.fastgen_enable_timing(self._ctx, int(enable)))
 
     def fastgen_read_timing(self) -> Dict[str, Tuple[float, int]]:
         ms = (ctypes.c_double * len(PHASES))()

@@ -114,23 +114,30 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <class T>
 T* at(fastgen_ctx* ctx, size_t off) { return reinterpret_cast<T*>(ctx->ws + off); }
 
-// Brackets one kernel group with events when device-time accounting is on.
-struct PhaseTimer {
-  fastgen_ctx* ctx; hipStream_t s; fastgen_ctx::timed rec; bool on;
-  PhaseTimer(fastgen_ctx* c, int phase, hipStream_t st) : ctx(c), s(st), on(c->timing) {
-    if (!on) return;
-    rec.phase = phase;
-    hipEvent_t* ev[2] = {&rec.a, &rec.b};
-    for (auto e : ev) {
-      if (!ctx->spare.empty()) { *e = ctx->spare.back(); ctx->spare.pop_back(); }
-      else if (hipEventCreate(e) != hipSuccess) { on = false; return; }
-    }
-    (void)hipEventRecord(rec.a, s);
+// Device-time accounting of the kernel groups of one API call: consecutive groups share the
+// event between them (an event record costs several microseconds on the stream).
+struct PhaseChain {
+  fastgen_ctx* ctx; hipStream_t s; bool on; int last = -1, open_phase = -1, open_a = -1;
+  PhaseChain(fastgen_ctx* c, hipStream_t st, bool enabled) : ctx(c), s(st), on(enabled) {}
+  int record() {
+    hipEvent_t e;
+    if (!ctx->spare.empty()) { e = ctx->spare.back(); ctx->spare.pop_back(); }
+    else if (hipEventCreate(&e) != hipSuccess) { on = false; return -1; }
+    (void)hipEventRecord(e, s);
+    ctx->events.push_back(e);
+    return (int)ctx->events.size() - 1;
   }
-  ~PhaseTimer() {
+  void begin(int phase) {
     if (!on) return;
-    (void)hipEventRecord(rec.b, s);
-    ctx->pending.push_back(rec);
+    open_a = last >= 0 ? last : record();
+    open_phase = phase;
+  }
+  void end() {
+    if (!on || open_phase < 0) return;
+    const int b = record();
+    if (b >= 0 && open_a >= 0) ctx->pending.push_back({open_phase, open_a, b});
+    last = b;
+    open_phase = -1;
   }
 };
 
@@ -153,7 +160,7 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
   if (bytes < lay.total) return FG_ENOMEM;
   fastgen_ctx* ctx = new (std::nothrow) fastgen_ctx();
   if (!ctx) return FG_ENOMEM;
-  ctx->timing = false;
+  ctx->timing = 0;
   ctx->cfg = *cfg;
   ctx->lay = lay;
   ctx->ws = static_cast<char*>(workspace);
@@ -169,7 +176,7 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
 
 fg_status fastgen_destroy(fastgen_ctx* ctx) {
   if (!ctx) return FG_OK;
-  for (auto& r : ctx->pending) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (auto e : ctx->events) (void)hipEventDestroy(e);
   for (auto e : ctx->spare) (void)hipEventDestroy(e);
   delete ctx;
   return FG_OK;
@@ -177,7 +184,7 @@ fg_status fastgen_destroy(fastgen_ctx* ctx) {
 
 fg_status fastgen_enable_timing(fastgen_ctx* ctx, int enable) {
   if (!ctx) return FG_EINVAL;
-  ctx->timing = enable != 0;
+  ctx->timing = enable < 0 ? 0 : enable;
   return FG_OK;
 }
 
@@ -188,13 +195,13 @@ fg_status fastgen_read_timing(fastgen_ctx* ctx, double* ms, int64_t* launches) {
   fg_status st = FG_OK;
   for (auto& r : ctx->pending) {
     float t = 0.f;
-    hipError_t e = hipEventSynchronize(r.b);
-    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.a, r.b);
+    hipError_t e = hipEventSynchronize(ctx->events[r.b]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, ctx->events[r.a], ctx->events[r.b]);
     if (e != hipSuccess) st = hip_fail(ctx, e, "fastgen_read_timing");
     else { ms[r.phase] += (double)t; if (launches) launches[r.phase] += 1; }
-    ctx->spare.push_back(r.a);
-    ctx->spare.push_back(r.b);
   }
+  for (auto e : ctx->events) ctx->spare.push_back(e);
+  ctx->events.clear();
   ctx->pending.clear();
   return st;
 }
@@ -218,15 +225,18 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w; pa.G = group_of(c);
   pa.scale = ctx->scale;
   hipError_t e;
+  PhaseChain tm(ctx, s, ctx->timing != 0);
   {
-    PhaseTimer tm(ctx, FG_PHASE_SWEEP1, s);
+    tm.begin(FG_PHASE_SWEEP1);
     if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * pa.G * c.prompt_len, s);
     else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
+    tm.end();
   }
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(row log-sum-exp sweep)");
   {
-    PhaseTimer tm(ctx, FG_PHASE_SWEEP2, s);
+    tm.begin(FG_PHASE_SWEEP2);
     e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 2, s) : fg_launch_profile_f32(pa, 2, s);
+    tm.end();
   }
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(column sweep)");
 
@@ -242,8 +252,9 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   sa.forced_policy = c.forced_policy;
   family_of(c, sa.family);
   {
-    PhaseTimer tm(ctx, FG_PHASE_SELECT, s);
+    tm.begin(FG_PHASE_SELECT);
     e = fg_launch_select(sa, s);
+    tm.end();
   }
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(select)");
   ctx->stage = 1;
@@ -258,7 +269,8 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   const fg_config& c = ctx->cfg;
   const fg_layout& L = ctx->lay;
-  PhaseTimer tm(ctx, FG_PHASE_COMPACT, s);
+  PhaseChain tm(ctx, s, ctx->timing != 0);
+  tm.begin(FG_PHASE_COMPACT);
   hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int32_t>(ctx, L.len), at<int64_t>(ctx, L.off),
                                    at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
                                    at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
@@ -279,6 +291,7 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   ca.units_per_seq = c.num_units / c.num_seqs;
   ca.pool_tokens = L.pool_tokens;
   e = fg_launch_compact(ca, s);
+  tm.end();
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(gather)");
   ctx->stage = 2;
   ctx->steps_done = 0;
@@ -315,15 +328,14 @@ static fg_status decode_step_impl(fastgen_ctx* ctx, const void* q, const void* k
   family_of(c, da.family);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  {
-    PhaseTimer tm(ctx, FG_PHASE_DECODE_ATTN, s);
-    e = fg_launch_decode_attn(da, s);
-  }
+  PhaseChain tm(ctx, s, ctx->timing == 1 || (ctx->timing > 1 && ctx->steps_done % ctx->timing == 0));
+  tm.begin(FG_PHASE_DECODE_ATTN);
+  e = fg_launch_decode_attn(da, s);
+  tm.end();
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step(attention)");
-  {
-    PhaseTimer tm(ctx, FG_PHASE_DECODE_UPDATE, s);
-    e = fg_launch_decode_update(da, s);
-  }
+  tm.begin(FG_PHASE_DECODE_UPDATE);
+  e = fg_launch_decode_update(da, s);
+  tm.end();
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_decode_step(update)");
   ctx->steps_done += 1;
   return FG_OK;

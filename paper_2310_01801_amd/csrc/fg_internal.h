@@ -52,9 +52,12 @@ struct fastgen_ctx {
   int steps_done;
   char err[256];
   // optional device-time accounting
-  bool timing;
-  struct timed { int phase; hipEvent_t a, b; };
+  // 0 off; 1 every kernel group; N > 1: the prompt-time phases always, a decode step when
+  // its index is a multiple of N
+  int timing;
+  struct timed { int phase; int a, b; };   // indices into `events`
   std::vector<timed> pending;
+  std::vector<hipEvent_t> events;          // recorded since the last read
   std::vector<hipEvent_t> spare;
 };
 
