@@ -36,8 +36,8 @@ MEASURED_TRAFFIC = {
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_b1")
     ap.add_argument("--decode-steps", type=int, default=-1, help="override S (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
