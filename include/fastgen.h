@@ -125,6 +125,29 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K,
                           const uint8_t* token_class, const float* lse_opt, int32_t* policy,
                           double* recovery, int32_t* kept_count, void* stream);
 
+/* Stage 1a for callers that cannot allocate device memory and hold no workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): fastgen_profile without
+ * a context. The scratch its kernels need (row log-sum-exps, column and band sums, kept flags,
+ * per-unit results) lives in a static device array of 32 MiB inside the library, one copy per
+ * GPU, held until the process ends; the call allocates nothing, on the host or the device.
+ *   cfg          the configuration fastgen_create would take (max_new_tokens and cache_tokens
+ *                only size the slot reservation and do not matter here). The shape is limited
+ *                by the array: U * n * (4 * G + 21) + 112 * U bytes, each of the twelve regions
+ *                rounded up to 256 bytes, must not exceed 32 MiB (e.g. U * n <= 1.3 M tokens at
+ *                G = 1); larger shapes return FG_ENOMEM and launch nothing.
+ *   Q, K, token_class, lse_opt, policy, recovery, kept_count, stream: as for fastgen_profile;
+ *                the caller owns inputs and outputs. The device that owns `stream` must be the
+ *                current device.
+ * Results are the same as fastgen_profile's for the same inputs. Every call on one GPU uses
+ * that GPU's one array: calls that overlap on a GPU (two streams, two threads) race; calls on
+ * one stream are ordered. Nothing of a previous call is read. There is no context to compact
+ * from: follow with fastgen_create / fastgen_profile when the cache is wanted. On failure
+ * fastgen_last_error(NULL) returns the message (per host thread). */
+fg_status fastgen_profile_static(const fg_config* cfg, const void* Q, const void* K,
+                                 const uint8_t* token_class, const float* lse_opt,
+                                 int32_t* policy, double* recovery, int32_t* kept_count,
+                                 void* stream);
+
 /* Stage 1b -- compaction f(K, V, C) (Alg. 1): copies the rows of K, V [U, n, d] that the
  * unit's policy keeps into the context's ragged cache (ascending position), together with
  * each kept token's cumulative attention score, position and class. Needs a preceding
@@ -193,7 +216,8 @@ fg_status fastgen_enable_timing(fastgen_ctx* ctx, int enable);
 fg_status fastgen_read_timing(fastgen_ctx* ctx, double* ms, int64_t* launches);
 
 /* Message for the last non-OK status returned on this context ("" if none). The string is
- * owned by the context and valid until the next call on it. */
+ * owned by the context and valid until the next call on it. With ctx == NULL: the message of
+ * the calling thread's last failed fastgen_profile_static. */
 const char* fastgen_last_error(const fastgen_ctx* ctx);
 
 /* Library version string (static storage). */

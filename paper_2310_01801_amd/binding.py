@@ -23,7 +23,7 @@ STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_E
 EXPORTED = (
     "fastgen_workspace_bytes", "fastgen_create", "fastgen_destroy", "fastgen_profile",
     "fastgen_compact", "fastgen_decode_step", "fastgen_decode_step_probe", "fastgen_export_state", "fastgen_last_error",
-    "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing",
+    "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing", "fastgen_profile_static",
 )
 PHASES = ("sweep1", "sweep2", "select", "compact", "decode_attn", "decode_update")
 
@@ -63,6 +63,8 @@ def load_library() -> ctypes.CDLL:
     lib.fastgen_destroy.argtypes = [vp]
     lib.fastgen_profile.restype = ctypes.c_int
     lib.fastgen_profile.argtypes = [vp] * 9
+    lib.fastgen_profile_static.restype = ctypes.c_int
+    lib.fastgen_profile_static.argtypes = [cp] + [vp] * 8
     lib.fastgen_compact.restype = ctypes.c_int
     lib.fastgen_compact.argtypes = [vp] * 4
     lib.fastgen_decode_step.restype = ctypes.c_int
@@ -107,6 +109,18 @@ def make_config(num_units: int, num_seqs: int, head_dim: int, dtype: torch.dtype
 
 def fastgen_workspace_bytes(cfg: FgConfig) -> int:
     return int(load_library().fastgen_workspace_bytes(ctypes.byref(cfg)))
+
+
+def fastgen_profile_static(cfg: FgConfig, Q: torch.Tensor, K: torch.Tensor, token_class: torch.Tensor,
+                           policy: torch.Tensor, recovery: torch.Tensor, kept_count: torch.Tensor,
+                           lse: Optional[torch.Tensor] = None) -> None:
+    """fastgen_profile without a context or a workspace (the library's static scratch array).
+    The caller passes the output tensors: this wrapper allocates nothing either."""
+    lib = load_library()
+    st = lib.fastgen_profile_static(ctypes.byref(cfg), _ptr(Q), _ptr(K), _ptr(token_class), _ptr(lse),
+                                    _ptr(policy), _ptr(recovery), _ptr(kept_count), _stream())
+    if st != FG_OK:
+        raise FastGenError(st, lib.fastgen_last_error(None).decode())
 
 
 class FastGen:

@@ -6,14 +6,27 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "fg_common.h"
 #include "fg_internal.h"
 
+// Scratch of fastgen_profile_static, the entry point that allocates nothing: one copy of this
+// array lives on every GPU the library runs on, from module load until the process ends. In
+// host code the name `scratch` is only a handle for hipGetSymbolAddress; the device address it
+// yields (one per GPU) is what kernels and copies receive.
+static constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch`, per GPU (NULL: not asked yet)
+static std::mutex g_scratch_mu;
+static thread_local char g_static_err[256] = "";
+
 namespace {
 
 constexpr size_t kAlign = 256;
+
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 bool config_ok(const fg_config* c, char* why, size_t why_len) {
@@ -58,16 +71,11 @@ void family_of(const fg_config& c, int* out) {
 
 int group_of(const fg_config& c) { return c.group_size > 1 ? c.group_size : 1; }
 
-fg_layout make_layout(const fg_config& c) {
-  fg_layout L;
-  memset(&L, 0, sizeof(L));
+// Regions that fastgen_profile writes (the profiling scratch and the per-unit results); they
+// come first in the workspace. Returns the bytes they take.
+size_t layout_profile_part(const fg_config& c, fg_layout& L) {
   const size_t G = (size_t)group_of(c);
-  const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len, d = (size_t)c.head_dim;
-  const size_t e = c.dtype == FG_BF16 ? 2 : 4;
-  const size_t full = n + (size_t)c.max_new_tokens;
-  const size_t pool = c.cache_tokens > 0 ? (size_t)c.cache_tokens : U * full;
-  L.pool_tokens = (int64_t)pool;
-  L.max_chunks = (int64_t)(pool / FG_DECODE_CHUNK + U);
+  const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.lse2 = take(U * G * n * 4);
@@ -82,6 +90,21 @@ fg_layout make_layout(const fg_config& c) {
   L.off = take((U + 1) * 8);
   L.len = take(U * 4);
   L.flags = take(8 * 4);
+  return o;
+}
+
+fg_layout make_layout(const fg_config& c) {
+  fg_layout L;
+  memset(&L, 0, sizeof(L));
+  const size_t G = (size_t)group_of(c);
+  const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len, d = (size_t)c.head_dim;
+  const size_t e = c.dtype == FG_BF16 ? 2 : 4;
+  const size_t full = n + (size_t)c.max_new_tokens;
+  const size_t pool = c.cache_tokens > 0 ? (size_t)c.cache_tokens : U * full;
+  L.pool_tokens = (int64_t)pool;
+  L.max_chunks = (int64_t)(pool / FG_DECODE_CHUNK + U);
+  size_t o = layout_profile_part(c, L);
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.ck = take(pool * d * e);
   L.cv = take(pool * d * e);
   L.cscore = take(pool * 8);
@@ -102,6 +125,15 @@ fg_status fail(fastgen_ctx* ctx, fg_status st, const char* fmt, ...) {
     vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
     va_end(ap);
   }
+  return st;
+}
+
+// failure of a call that has no context: the message is kept per host thread
+__attribute__((format(printf, 2, 3))) fg_status sfail(fg_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_static_err, sizeof(g_static_err), fmt, ap);
+  va_end(ap);
   return st;
 }
 
@@ -141,6 +173,61 @@ struct PhaseChain {
   }
 };
 
+// The kernels of stage 1a in launch order, over scratch regions `L` inside `ws`. Shared by
+// fastgen_profile (regions in the caller's workspace) and fastgen_profile_static (regions in
+// the library's own static device array).
+hipError_t launch_profile_path(const fg_config& c, const fg_layout& L, char* ws, float scale, int w,
+                               const void* Q, const void* K, const uint8_t* token_class,
+                               const float* lse_opt, int32_t* policy, double* recovery,
+                               int32_t* kept_count, hipStream_t s, PhaseChain& tm, const char** where) {
+  auto at = [&](size_t off) { return ws + off; };
+  fg_profile_args pa;
+  pa.Q = Q; pa.K = K;
+  pa.lse2 = reinterpret_cast<float*>(at(L.lse2));
+  pa.colsum = reinterpret_cast<double*>(at(L.colsum));
+  pa.bandcol = reinterpret_cast<double*>(at(L.bandcol));
+  pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = w; pa.G = group_of(c);
+  pa.scale = scale;
+  hipError_t e;
+  *where = "fastgen_profile(row log-sum-exp sweep)";
+  tm.begin(FG_PHASE_SWEEP1);
+  if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * pa.G * c.prompt_len, s);
+  else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
+  tm.end();
+  if (e != hipSuccess) return e;
+  *where = "fastgen_profile(column sweep)";
+  tm.begin(FG_PHASE_SWEEP2);
+  e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 2, s) : fg_launch_profile_f32(pa, 2, s);
+  tm.end();
+  if (e != hipSuccess) return e;
+
+  fg_select_args sa;
+  sa.colsum = pa.colsum; sa.bandcol = pa.bandcol; sa.token_class = token_class;
+  sa.keep = reinterpret_cast<uint8_t*>(at(L.keep)); sa.slot = reinterpret_cast<int32_t*>(at(L.slot));
+  sa.policy = reinterpret_cast<int32_t*>(at(L.policy)); sa.recov = reinterpret_cast<double*>(at(L.recov));
+  sa.kcount = reinterpret_cast<int32_t*>(at(L.kcount)); sa.cap = reinterpret_cast<int32_t*>(at(L.cap));
+  sa.len = reinterpret_cast<int32_t*>(at(L.len));
+  sa.policy_out = policy; sa.recov_out = recovery; sa.kcount_out = kept_count;
+  sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
+  sa.w = w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f; sa.G = pa.G;
+  sa.forced_policy = c.forced_policy;
+  family_of(c, sa.family);
+  *where = "fastgen_profile(select)";
+  tm.begin(FG_PHASE_SELECT);
+  e = fg_launch_select(sa, s);
+  tm.end();
+  return e;
+}
+
+float scale_of(const fg_config& c) {
+  return c.softmax_scale > 0.f ? c.softmax_scale : 1.0f / sqrtf((float)c.head_dim);
+}
+
+int window_of(const fg_config& c) {
+  const int w = fg_budget(c.r_l, c.prompt_len);
+  return w < 1 ? 1 : w;
+}
+
 }  // namespace
 
 extern "C" {
@@ -164,9 +251,8 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
   ctx->cfg = *cfg;
   ctx->lay = lay;
   ctx->ws = static_cast<char*>(workspace);
-  ctx->scale = cfg->softmax_scale > 0.f ? cfg->softmax_scale : 1.0f / sqrtf((float)cfg->head_dim);
-  const int w = fg_budget(cfg->r_l, cfg->prompt_len);
-  ctx->w = w < 1 ? 1 : w;
+  ctx->scale = scale_of(*cfg);
+  ctx->w = window_of(*cfg);
   ctx->stage = 0;
   ctx->steps_done = 0;
   ctx->err[0] = '\0';
@@ -214,50 +300,53 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const 
   if (!aligned16(Q) || !aligned16(K)) return fail(ctx, FG_EINVAL, "fastgen_profile: Q and K must be 16-byte aligned");
   if (ctx->stage != 0) return fail(ctx, FG_ESTATE, "fastgen_profile: context already profiled");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const fg_config& c = ctx->cfg;
-  const fg_layout& L = ctx->lay;
-
-  fg_profile_args pa;
-  pa.Q = Q; pa.K = K;
-  pa.lse2 = at<float>(ctx, L.lse2);
-  pa.colsum = at<double>(ctx, L.colsum);
-  pa.bandcol = at<double>(ctx, L.bandcol);
-  pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = ctx->w; pa.G = group_of(c);
-  pa.scale = ctx->scale;
-  hipError_t e;
   PhaseChain tm(ctx, s, ctx->timing != 0);
-  {
-    tm.begin(FG_PHASE_SWEEP1);
-    if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * pa.G * c.prompt_len, s);
-    else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
-    tm.end();
-  }
-  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(row log-sum-exp sweep)");
-  {
-    tm.begin(FG_PHASE_SWEEP2);
-    e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 2, s) : fg_launch_profile_f32(pa, 2, s);
-    tm.end();
-  }
-  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(column sweep)");
-
-  fg_select_args sa;
-  sa.colsum = pa.colsum; sa.bandcol = pa.bandcol; sa.token_class = token_class;
-  sa.keep = at<uint8_t>(ctx, L.keep); sa.slot = at<int32_t>(ctx, L.slot);
-  sa.policy = at<int32_t>(ctx, L.policy); sa.recov = at<double>(ctx, L.recov);
-  sa.kcount = at<int32_t>(ctx, L.kcount); sa.cap = at<int32_t>(ctx, L.cap);
-  sa.len = at<int32_t>(ctx, L.len);
-  sa.policy_out = policy; sa.recov_out = recovery; sa.kcount_out = kept_count;
-  sa.U = c.num_units; sa.n = c.prompt_len; sa.units_per_seq = c.num_units / c.num_seqs;
-  sa.w = ctx->w; sa.S = c.max_new_tokens; sa.T = c.T; sa.r_f = c.r_f; sa.G = pa.G;
-  sa.forced_policy = c.forced_policy;
-  family_of(c, sa.family);
-  {
-    tm.begin(FG_PHASE_SELECT);
-    e = fg_launch_select(sa, s);
-    tm.end();
-  }
-  if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_profile(select)");
+  const char* where = "";
+  const hipError_t e = launch_profile_path(ctx->cfg, ctx->lay, ctx->ws, ctx->scale, ctx->w, Q, K, token_class,
+                                           lse_opt, policy, recovery, kept_count, s, tm, &where);
+  if (e != hipSuccess) return hip_fail(ctx, e, where);
   ctx->stage = 1;
+  return FG_OK;
+}
+
+fg_status fastgen_profile_static(const fg_config* cfg, const void* Q, const void* K,
+                                 const uint8_t* token_class, const float* lse_opt, int32_t* policy,
+                                 double* recovery, int32_t* kept_count, void* stream) {
+  char why[128] = "";
+  if (!config_ok(cfg, why, sizeof(why))) return sfail(FG_EINVAL, "fastgen_profile_static: %s", why);
+  if (!Q || !K || !token_class) return sfail(FG_EINVAL, "fastgen_profile_static: Q, K and token_class are required");
+  if (!aligned16(Q) || !aligned16(K)) return sfail(FG_EINVAL, "fastgen_profile_static: Q and K must be 16-byte aligned");
+  fg_layout L;
+  memset(&L, 0, sizeof(L));
+  const size_t need = layout_profile_part(*cfg, L);
+  if (need > kStaticScratchBytes)
+    return sfail(FG_ENOMEM, "fastgen_profile_static: this shape needs %zu bytes of scratch, the static array holds %zu",
+                 need, kStaticScratchBytes);
+  // device address of this GPU's copy of the array (asked once per device, with it current)
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return sfail(FG_EHIP, "fastgen_profile_static(hipGetDevice): %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return sfail(FG_EINVAL, "fastgen_profile_static: device index %d not supported", dev);
+  void* base = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return sfail(FG_EHIP, "fastgen_profile_static(hipGetSymbolAddress): %s", hipGetErrorString(e));
+      g_scratch_ptr[dev] = p;
+    }
+    base = g_scratch_ptr[dev];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  PhaseChain tm(nullptr, s, false);
+  const char* where = "";
+  // every region the kernels read is written first by an earlier kernel of this call for all
+  // U * n entries in use, so nothing left over from the previous call needs clearing
+  e = launch_profile_path(*cfg, L, static_cast<char*>(base), scale_of(*cfg), window_of(*cfg), Q, K, token_class,
+                          lse_opt, policy, recovery, kept_count, s, tm, &where);
+  if (e != hipSuccess) return sfail(FG_EHIP, "%s: %s", where, hipGetErrorString(e));
   return FG_OK;
 }
 
@@ -379,7 +468,7 @@ fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offs
   return FG_OK;
 }
 
-const char* fastgen_last_error(const fastgen_ctx* ctx) { return ctx ? ctx->err : "context is NULL"; }
+const char* fastgen_last_error(const fastgen_ctx* ctx) { return ctx ? ctx->err : g_static_err; }
 
 const char* fastgen_version(void) { return "fastgen-mi355x 0.1 (gfx950)"; }
 

@@ -76,3 +76,19 @@ def test_create_and_call_order_errors_without_launching(lib):
     assert lib.fastgen_export_state(ctx, None, None, None, None, None, None, None, None) == binding.FG_ESTATE
     assert lib.fastgen_destroy(ctx) == binding.FG_OK
     assert lib.fastgen_destroy(None) == binding.FG_OK
+
+
+def test_static_profile_rejects_bad_arguments_on_the_host(lib):
+    fake = 0x10000  # never dereferenced: every call below fails before anything is launched
+    cfg = _cfg()
+    call = lib.fastgen_profile_static
+    assert call(None, fake, fake, fake, None, None, None, None, None) == binding.FG_EINVAL
+    assert b"config is NULL" in lib.fastgen_last_error(None)
+    assert call(ctypes.byref(_cfg(head_dim=96)), fake, fake, fake, None, None, None, None, None) == binding.FG_EINVAL
+    assert call(ctypes.byref(cfg), None, fake, fake, None, None, None, None, None) == binding.FG_EINVAL
+    assert call(ctypes.byref(cfg), fake + 4, fake, fake, None, None, None, None, None) == binding.FG_EINVAL
+    assert b"16-byte aligned" in lib.fastgen_last_error(None)
+    # beyond the static scratch array (32 MiB): refused with the sizes in the message
+    big = _cfg(num_units=1024, num_seqs=1, prompt_len=2048)
+    assert call(ctypes.byref(big), fake, fake, fake, None, None, None, None, None) == binding.FG_ENOMEM
+    assert b"static array holds 33554432" in lib.fastgen_last_error(None)
