@@ -1,0 +1,234 @@
+"""Pins for the quantities that decide which units a parity test sets aside, and a self-test
+of the parity harness. A slip in any of them would silently switch comparisons off, so each
+is checked here against exact rationals or a hand-built case, on the CPU:
+
+  * Profile.margin      min over the usable family members of |R_c - T|   (Eq. 1 threshold)
+  * Profile.topk_gap    relative gap at the frequent policy's top-k boundary (Sec. 3.4)
+  * Cache.min_gap / fragile_step   the same gap while decoding, and the first step it falls
+                                    below the harness's band
+  * fg_harness.compare  must raise when the device side reports a wrong policy, kept set,
+                        recovery, score, output or probe value.
+"""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fastgen_oracle as fo
+from paper_2310_01801_amd import synth
+import fg_harness as H
+
+
+def harmonic(k):
+    return sum(Fraction(1, i) for i in range(1, k + 1))
+
+
+# ---------------------------------------------------------------- margin (Eq. 1)
+
+def _uniform_unit(n, d=8):
+    """Q = 0: uniform causal attention A_ij = 1/(i+1), every recovery an exact rational."""
+    cls = np.zeros(n, dtype=np.uint8)
+    cls[0] = 1
+    return np.zeros((n, d)), np.ones((n, d)), cls
+
+
+def test_margin_is_distance_of_nearest_usable_recovery_to_T():
+    # n = 4, special = {0}, k_f = 2, w = 1: R = 25/48, 25/48, 38/48, 45/48, 1 (worked example)
+    Q, K, cls = _uniform_unit(4)
+    R = [Fraction(25, 48), Fraction(25, 48), Fraction(38, 48), Fraction(45, 48)]
+    for T in (0.8, 0.5, 0.93, float(Fraction(38, 48)) + 5e-5, float(Fraction(38, 48)) - 2e-4):
+        p = fo.profile_unit(Q, K, cls, T, 0.25, 0.5, 1.0)
+        want = min(abs(float(r) - T) for r in R)
+        assert abs(p.margin - want) < 1e-15, (T, p.margin, want)
+    # the harness's rule: below 1e-4 the policy choice itself is within float error
+    assert fo.profile_unit(Q, K, cls, float(Fraction(38, 48)) + 5e-5, 0.25, 0.5, 1.0).margin < H.MARGIN_EPS
+    assert fo.profile_unit(Q, K, cls, float(Fraction(38, 48)) + 2e-4, 0.25, 0.5, 1.0).margin > H.MARGIN_EPS
+    # C_full (recovery exactly 1) never counts: T = 1 is not "within margin" of it
+    assert fo.profile_unit(Q, K, cls, 1.0, 0.25, 0.5, 1.0).margin == pytest.approx(1 - 45 / 48, abs=1e-15)
+
+
+def test_margin_ignores_unused_family_entries():
+    Q, K, cls = _uniform_unit(4)
+    # table {special, unused, special+frequent, unused}: only 25/48 and 38/48 can decide
+    fam = (fo.SPECIAL, 0, fo.SPECIAL | fo.FREQUENT, 0)
+    T = 45 / 48          # the full family would have margin 0 here
+    p = fo.profile_unit(Q, K, cls, T, 0.25, 0.5, 1.0, family=fam)
+    assert p.margin == pytest.approx(T - 38 / 48, abs=1e-15)
+    assert fo.profile_unit(Q, K, cls, T, 0.25, 0.5, 1.0).margin < 1e-15
+
+
+# ---------------------------------------------------------------- top-k boundary gap (Sec. 3.4)
+
+def test_boundary_gap_definition_and_edges():
+    s = np.array([0.5, 4.0, 1.0, 3.0, 2.0])
+    assert fo.boundary_gap(s, 2) == pytest.approx((3.0 - 2.0) / 3.0, abs=1e-16)   # 2nd vs 3rd largest
+    assert fo.boundary_gap(s, 4) == pytest.approx((1.0 - 0.5) / 1.0, abs=1e-16)
+    assert fo.boundary_gap(s, 0) == math.inf and fo.boundary_gap(s, 5) == math.inf and fo.boundary_gap(s, 9) == math.inf
+    assert fo.boundary_gap(np.array([2.0, 1.0, 1.0, 0.0]), 2) == 0.0               # an exact tie
+    assert fo.boundary_gap(np.array([0.0, 0.0, 0.0]), 1) == 0.0                    # nothing to divide by
+    # order of the inputs does not matter
+    rng = np.random.default_rng(3)
+    x = rng.random(50)
+    assert fo.boundary_gap(x, 17) == fo.boundary_gap(rng.permutation(x), 17)
+
+
+@pytest.mark.parametrize("n,r_f", [(12, 0.25), (40, 0.3), (64, 0.5)])
+def test_profile_topk_gap_closed_form_for_uniform_attention(n, r_f):
+    # colsum_j = H_n - H_j (0-based j) decreases with j: the k-th largest is column k-1, the
+    # next one column k, and their difference is exactly 1/k
+    Q, K, cls = _uniform_unit(n)
+    p = fo.profile_unit(Q, K, cls, 0.9, 0.1, r_f, 1.0)
+    k = math.floor(r_f * n)
+    assert p.k_f == k
+    want = Fraction(1, k) / (harmonic(n) - harmonic(k - 1))
+    assert p.topk_gap == pytest.approx(float(want), rel=1e-12)
+    # and it is the gap of the *column sums* at *this* budget: another budget gives another value
+    assert p.topk_gap != pytest.approx(float(Fraction(1, k + 1) / (harmonic(n) - harmonic(k))), rel=1e-6)
+
+
+# ---------------------------------------------------------------- decode-time gap and first fragile step
+
+def _planted_cache(eps):
+    """Eight prompt tokens, policy = frequent + local with w = 8 and r_f = 0.5, zero keys: with
+    q = 0 every held token receives 1/#held per step. Scores 10, 9, 8, 7, 6, 6 - eps, 1, 0.5."""
+    n = 8
+    score = np.array([10.0, 9.0, 8.0, 7.0, 6.0, 6.0 - eps, 1.0, 0.5])
+    return fo.Cache(policy=0, n=n, K=np.zeros((n, 4)), V=np.zeros((n, 4)), score=score,
+                    pos=np.arange(n, dtype=np.int64), cls=np.zeros(n, dtype=np.uint8),
+                    mask=fo.FREQUENT | fo.LOCAL)
+
+
+def _run_planted(eps, gap_eps, steps=3):
+    c = _planted_cache(eps)
+    z = np.zeros(4)
+    gaps = []
+    for t in range(steps):
+        fo.decode_step(c, z, z, z, 0, t, 1.0, 0.5, 1.0, gap_eps)
+        gaps.append(c.min_gap)
+    return c, gaps
+
+
+def test_fragile_step_rises_at_the_step_where_the_planted_pair_reaches_the_boundary():
+    eps = 1e-6
+    # step 0: 9 held, k_f = 4, boundary between 7 + 1/9 and 6 + 1/9            -> gap 1 / (7 + 1/9)
+    # step 1: 10 held (position 0 stays through its score, the rest through the window),
+    #         k_f = 5, boundary between 6 + 1/9 + 1/10 and 6 - eps + 1/9 + 1/10  -> gap eps / (6 + 19/90)
+    g0 = float(Fraction(1) / (7 + Fraction(1, 9)))
+    g1 = eps / float(6 + Fraction(19, 90))
+    c, gaps = _run_planted(eps, gap_eps=2e-5)
+    assert gaps[0] == pytest.approx(g0, rel=1e-12)
+    # step 2: 11 held, k_f = 5 again: the same pair, both scores larger by 1/11
+    g2 = eps / float(6 + Fraction(19, 90) + Fraction(1, 11))
+    assert gaps[1] == pytest.approx(g1, rel=1e-6) and gaps[2] == pytest.approx(g2, rel=1e-6)
+    assert c.fragile_step == 1                                                # not 0, not 2
+    # a band narrower than the planted gap: never flagged; min_gap is still reported
+    c, gaps = _run_planted(eps, gap_eps=g1 * 0.5)
+    assert c.fragile_step == -1 and gaps[1] == pytest.approx(g1, rel=1e-6)
+    # a pair ten times wider than the band: not flagged either
+    c, _ = _run_planted(1e-3, gap_eps=2e-5)
+    assert c.fragile_step == -1
+    # a band wide enough for step 0's gap: flagged at step 0 and never moved afterwards
+    c, _ = _run_planted(eps, gap_eps=0.2)
+    assert c.fragile_step == 0
+
+
+def test_gap_is_not_tracked_for_policies_without_frequent():
+    c = _planted_cache(1e-9)
+    c.mask = fo.LOCAL
+    z = np.zeros(4)
+    for t in range(3):
+        fo.decode_step(c, z, z, z, 0, t, 1.0, 0.5, 1.0, 1.0)
+    assert c.fragile_step == -1 and c.min_gap == math.inf
+
+
+# ---------------------------------------------------------------- the harness must be able to fail
+
+class FakeRun:
+    """Stands in for the device side of fg_harness.compare: answers come from a second oracle
+    run, optionally with one planted mistake."""
+
+    def __init__(self, w, mistake=None, forced_policy=-1):
+        self.w, self.units, self.device = w, list(range(w.num_units)), "cpu"
+        self.G, self.forced, self.family = 1, forced_policy, fo.DEFAULT_FAMILY
+        plan = synth.unit_plan(w)
+        cls_p, cls_d = synth.token_classes(w)
+        self.Q, self.K, self.V = synth.prompt_batch(w, plan, cls_p, self.units)
+        self.q, self.k, self.v = synth.decode_batch(w, plan, cls_d, self.units)
+        seqs = [u // w.units_per_seq for u in self.units]
+        self.cls_u = torch.from_numpy(cls_p[seqs].copy())
+        self.cls_dec_u = torch.from_numpy(cls_d[:, seqs].copy())
+        self.mistake = mistake or {}
+        self.ref = [H.oracle_unit(self, i) for i in range(len(self.units))]
+        self.t = -1
+
+    def profile_and_compact(self):
+        pol = np.array([r["profile"].policy for r in self.ref], dtype=np.int32)
+        rec = np.stack([r["profile"].recovery for r in self.ref]).copy()
+        cnt = np.stack([r["profile"].cost for r in self.ref]).astype(np.int32)
+        if "policy" in self.mistake:
+            pol[0] = (pol[0] + 1) % 5
+        if "recovery" in self.mistake:
+            rec[0, 2] += 1e-3
+        if "count" in self.mistake:
+            cnt[0, 3] += 1
+        return pol, rec, cnt
+
+    def _held(self, i):
+        r = self.ref[i]
+        pos = r["init_pos"] if self.t < 0 else r["states"][self.t]
+        sc = r["profile"].colsum[pos] if self.t < 0 else r["score_states"][self.t]
+        pos, sc = pos.copy(), sc.copy()
+        if i == 0 and self.mistake.get("kept") == self.t and pos.size > 1:
+            missing = np.setdiff1d(np.arange(self.w.prompt_len + self.w.steps), pos)
+            pos[-2] = missing[missing < pos[-1]][-1] if np.any(missing < pos[-1]) else pos[-2]
+            pos.sort()
+        if i == 0 and self.mistake.get("score") == self.t and sc.size:
+            sc[0] *= 1.001
+        return pos, sc
+
+    def state(self, rows=False):
+        out = [self._held(i) for i in range(len(self.units))]
+        if not rows:
+            return out
+        off = np.concatenate([[0], np.cumsum([p.size for p, _ in out])])
+        keys = torch.cat([self.K[i][torch.as_tensor(p)] for i, (p, _) in enumerate(out)])
+        values = torch.cat([self.V[i][torch.as_tensor(p)] for i, (p, _) in enumerate(out)])
+        if "row" in self.mistake:
+            keys = keys.clone()
+            keys[0, 0] += 1
+        return out, off, keys, values
+
+    def step(self, t, probe=False):
+        self.t = t
+        out = torch.from_numpy(np.stack([r["outs"][t] for r in self.ref]))
+        if self.mistake.get("out") == t:
+            out[0, 0] += 0.1
+        if probe:
+            rho = torch.from_numpy(np.stack([r["probes"][t] for r in self.ref]).copy())
+            if self.mistake.get("probe") == t:
+                rho[0, 0] += 1e-3
+            return out, rho
+        return out
+
+
+W_SELF = synth.WORKLOADS["llama7b_b1"].scaled(name="selftest", layers=1, heads=5, batch=1, prompt_len=96,
+                                             steps=6, seed=404)
+
+
+def test_harness_passes_on_a_faithful_device_side():
+    run = FakeRun(W_SELF)
+    run.ref = [H.oracle_unit(run, i, probe={2}) for i in range(len(run.units))]
+    rep = H.compare(run, probe_steps=[2])
+    assert rep.units == 5 and rep.margin_excluded == 0 and rep.max_out_err < 1e-6   # float32 round trip of the outputs
+
+
+@pytest.mark.parametrize("mistake", [{"policy": 1}, {"recovery": 1}, {"count": 1}, {"kept": -1}, {"row": 1},
+                                     {"kept": 3}, {"score": 4}, {"out": 2}, {"probe": 2}])
+def test_harness_raises_on_a_planted_mistake(mistake):
+    # forced policy 3: every unit keeps scores and evicts, so every kind of mistake is visible
+    run = FakeRun(W_SELF, mistake, forced_policy=3)
+    run.ref = [H.oracle_unit(run, i, probe={2}) for i in range(len(run.units))]
+    with pytest.raises(AssertionError):
+        H.compare(run, probe_steps=[2])
