@@ -57,6 +57,9 @@ def test_margin_ignores_unused_family_entries():
     p = fo.profile_unit(Q, K, cls, T, 0.25, 0.5, 1.0, family=fam)
     assert p.margin == pytest.approx(T - 38 / 48, abs=1e-15)
     assert fo.profile_unit(Q, K, cls, T, 0.25, 0.5, 1.0).margin < 1e-15
+    # an unused entry recovers nothing (R = 0): near T = 0 it must not be what sets the margin
+    p = fo.profile_unit(Q, K, cls, 0.01, 0.25, 0.5, 1.0, family=fam)
+    assert p.margin == pytest.approx(25 / 48 - 0.01, abs=1e-15)
 
 
 # ---------------------------------------------------------------- top-k boundary gap (Sec. 3.4)
@@ -117,11 +120,14 @@ def test_fragile_step_rises_at_the_step_where_the_planted_pair_reaches_the_bound
     #         k_f = 5, boundary between 6 + 1/9 + 1/10 and 6 - eps + 1/9 + 1/10  -> gap eps / (6 + 19/90)
     g0 = float(Fraction(1) / (7 + Fraction(1, 9)))
     g1 = eps / float(6 + Fraction(19, 90))
-    c, gaps = _run_planted(eps, gap_eps=2e-5)
+    c, gaps = _run_planted(eps, gap_eps=2e-5, steps=4)
     assert gaps[0] == pytest.approx(g0, rel=1e-12)
     # step 2: 11 held, k_f = 5 again: the same pair, both scores larger by 1/11
     g2 = eps / float(6 + Fraction(19, 90) + Fraction(1, 11))
     assert gaps[1] == pytest.approx(g1, rel=1e-6) and gaps[2] == pytest.approx(g2, rel=1e-6)
+    # step 3: 12 held, k_f = 6: the boundary has moved below the pair (6.3 against 1.4), a wide
+    # gap again -- min_gap keeps the smallest one seen
+    assert gaps[3] == gaps[2]
     assert c.fragile_step == 1                                                # not 0, not 2
     # a band narrower than the planted gap: never flagged; min_gap is still reported
     c, gaps = _run_planted(eps, gap_eps=g1 * 0.5)
