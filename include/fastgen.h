@@ -78,7 +78,7 @@ typedef struct {
   int32_t head_dim;       /* d: 64 or 128                                                     */
   int32_t dtype;          /* fg_dtype of Q, K, V, q, k, v, out and of the cache               */
   int32_t prompt_len;     /* n >= 1, the same for every sequence                              */
-  int32_t max_new_tokens; /* S >= 0: decode steps the cache is sized for                      */
+  int32_t max_new_tokens; /* S >= 0: decode steps the cache is sized for; n + S <= 131072     */
   double T;               /* recovery threshold of Eq. 1, 0 < T <= 1                          */
   double r_l;             /* local window  w = max(1, floor(r_l * n))   (ratio of INPUT len)  */
   double r_f;             /* frequent budget k_f(L) = floor(r_f * L)    (ratio of CURRENT len)*/
@@ -162,7 +162,12 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
  *                    tokens including the new one.
  * After the output is formed the cumulative scores are updated (policies containing
  * `frequent`) and every unit's kept set is re-derived from its policy; evicted tokens are
- * released in place. FG_ECAP after max_new_tokens steps. */
+ * released in place. FG_ECAP after max_new_tokens steps.
+ * A cache pool that the caller made smaller than the reservations need (cfg.cache_tokens) is
+ * found on the device, during fastgen_compact: the host cannot know it without synchronising,
+ * so this call still returns FG_OK, its kernels return without touching memory and `out` is
+ * left unwritten. The `status` output of fastgen_export_state reports it (FG_ECAP); a caller
+ * that sets cache_tokens must read it once after fastgen_compact before trusting any output. */
 fg_status fastgen_decode_step(fastgen_ctx* ctx, const void* q, const void* k_new,
                               const void* v_new, const uint8_t* class_new, void* out,
                               void* stream);

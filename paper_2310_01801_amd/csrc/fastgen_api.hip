@@ -26,6 +26,7 @@ static thread_local char g_static_err[256] = "";
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int FG_MAX_TOKENS = 131072;  // longest sequence (prompt + generated) a unit may reach
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -40,14 +41,24 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
   FG_REQUIRE(c->num_seqs > 0 && c->num_units % c->num_seqs == 0, "num_seqs must divide num_units");
   FG_REQUIRE(c->head_dim == 64 || c->head_dim == 128, "head_dim must be 64 or 128");
   FG_REQUIRE(c->dtype == FG_F32 || c->dtype == FG_BF16, "dtype must be FG_F32 or FG_BF16");
-  FG_REQUIRE(c->prompt_len >= 1 && c->prompt_len <= (1 << 20), "prompt_len out of range");
-  FG_REQUIRE(c->max_new_tokens >= 0 && c->max_new_tokens <= (1 << 20), "max_new_tokens out of range");
+  FG_REQUIRE(c->prompt_len >= 1 && c->prompt_len <= FG_MAX_TOKENS, "prompt_len out of range");
+  FG_REQUIRE(c->max_new_tokens >= 0 && c->max_new_tokens <= FG_MAX_TOKENS, "max_new_tokens out of range");
+  // the kernels index a unit's rows with 32-bit byte offsets (16 heads x 131072 rows x 512 B is
+  // below 2^31) and the read-back kernel keeps a bitmap of n + S positions in shared memory
+  FG_REQUIRE(c->prompt_len + c->max_new_tokens <= FG_MAX_TOKENS,
+             "prompt_len + max_new_tokens must not exceed 131072");
   FG_REQUIRE(c->T > 0.0 && c->T <= 1.0, "T must be in (0, 1]");
   FG_REQUIRE(c->r_l >= 0.0 && c->r_l <= 1.0, "r_l must be in [0, 1]");
   FG_REQUIRE(c->r_f >= 0.0 && c->r_f <= 1.0, "r_f must be in [0, 1]");
   FG_REQUIRE(c->softmax_scale >= 0.f && isfinite(c->softmax_scale), "softmax_scale must be >= 0");
   FG_REQUIRE(c->forced_policy >= -1 && c->forced_policy <= 4, "forced_policy must be -1..4");
   FG_REQUIRE(c->cache_tokens >= 0, "cache_tokens must be >= 0");
+  {
+    // the flat work list of the decode kernels (one item per 256 reserved slots) is a 32-bit grid
+    const long long full = (long long)c->prompt_len + c->max_new_tokens;
+    const long long pool = c->cache_tokens > 0 ? c->cache_tokens : (long long)c->num_units * full;
+    FG_REQUIRE(pool / FG_DECODE_CHUNK + c->num_units < (1ll << 31) - 1, "cache pool too large for the decode work list");
+  }
   FG_REQUIRE(c->group_size >= 0 && c->group_size <= 16, "group_size must be 0..16");
   bool any = false;
   for (int i = 0; i < 4; ++i) {
@@ -452,8 +463,6 @@ fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offs
     return fail(ctx, FG_EINVAL, "fastgen_export_state: packed outputs need `offsets`");
   const fg_config& c = ctx->cfg;
   const fg_layout& L = ctx->lay;
-  if ((size_t)(c.prompt_len + c.max_new_tokens) > (size_t)200000)
-    return fail(ctx, FG_EINVAL, "fastgen_export_state: prompt_len + max_new_tokens too large for the read-back kernel");
   fg_export_args ea;
   ea.off = at<int64_t>(ctx, L.off); ea.len = at<int32_t>(ctx, L.len);
   ea.flags = at<int32_t>(ctx, L.flags);

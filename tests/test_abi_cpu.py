@@ -53,9 +53,17 @@ def test_workspace_bytes_and_validation(lib):
     assert binding.fastgen_workspace_bytes(_cfg(family=(8, 4, 12, 0), forced_policy=2)) == nbytes
     assert binding.fastgen_workspace_bytes(_cfg(group_size=4)) > nbytes   # per-head lse, logits, partials
     assert binding.fastgen_workspace_bytes(_cfg(group_size=0)) == nbytes
+    # the accepted maximum: 131072 tokens per unit, 16 query heads per K/V head, float32
+    big = _cfg(num_units=2, num_seqs=1, prompt_len=131000, max_new_tokens=72, group_size=16, dtype=binding.torch.float32)
+    assert binding.fastgen_workspace_bytes(big) > 2 * 131072 * 128 * 4 * 2
     for bad in (dict(head_dim=96), dict(num_seqs=3), dict(T=0.0), dict(T=1.5), dict(r_l=-0.1),
                 dict(prompt_len=0), dict(forced_policy=7), dict(num_units=0), dict(family=(1, 16, 0, 0)),
-                dict(family=(1, 0, 0, 8), forced_policy=1), dict(group_size=17), dict(group_size=-1)):
+                dict(family=(1, 0, 0, 8), forced_policy=1), dict(group_size=17), dict(group_size=-1),
+                # beyond what the kernels' 32-bit row offsets and the read-back bitmap cover
+                dict(prompt_len=131073, max_new_tokens=0), dict(prompt_len=131072, max_new_tokens=1),
+                dict(prompt_len=1 << 20), dict(max_new_tokens=1 << 20), dict(prompt_len=70000, max_new_tokens=70000),
+                # more work items than a 32-bit grid holds
+                dict(num_units=1 << 24, num_seqs=1, prompt_len=131072, max_new_tokens=0)):
         assert binding.fastgen_workspace_bytes(_cfg(**bad)) == 0, bad
 
 

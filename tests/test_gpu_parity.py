@@ -16,7 +16,15 @@ W = synth.WORKLOADS
 
 
 def _report(name, rep):
-    print(f"\n[parity] {name}: {rep.line()}", flush=True)
+    H.log_report(name, rep)
+
+
+def _covers_realised_policies(rep, pol_all, floor=0.05):
+    """Every policy that at least `floor` of ALL units of the run ended on (device histogram)
+    must be among the policies of the oracle-followed sample."""
+    hist = np.bincount(pol_all, minlength=5) / pol_all.size
+    common = {c for c in range(5) if hist[c] >= floor}
+    assert common <= set(rep.policies), (hist.tolist(), rep.policies)
 
 
 def test_tiny_config_all_units_every_step():
@@ -96,18 +104,17 @@ def test_determinism_bitwise():
 
 
 def test_supplied_lse_skips_first_sweep():
-    w = W["llama7b_b1"].scaled(name="lse", layers=1, heads=6, batch=1, prompt_len=320, steps=0, seed=13)
-    a = H.GpuRun(w, range(w.num_units))
-    pol_a, rec_a, cnt_a = a.profile_and_compact()
+    """A caller-supplied row log-sum-exp replaces sweep 1: policies, recoveries, kept sets,
+    compacted rows and the decode steps that follow are compared with the oracle as usual."""
+    w = W["llama7b_b1"].scaled(name="lse", layers=1, heads=6, batch=2, prompt_len=320, steps=12, seed=13)
+    run = H.GpuRun(w, range(w.num_units))
     # natural-log row LSE from plain torch in float64 (what a prefill kernel would hand over)
-    s = torch.einsum("uid,ujd->uij", a.Q.double(), a.K.double()) * H.scale_of(w)
+    s = torch.einsum("uid,ujd->uij", run.Q.double(), run.K.double()) * H.scale_of(w)
     mask = torch.triu(torch.ones(w.prompt_len, w.prompt_len, dtype=torch.bool, device=s.device), 1)
-    lse = torch.logsumexp(s.masked_fill(mask, float("-inf")), dim=2).float().contiguous()
-    b = H.GpuRun(w, range(w.num_units))
-    pol_b, rec_b, cnt_b = b.fg.fastgen_profile(b.Q, b.K, b.cls_u, lse=lse)
-    torch.cuda.synchronize()
-    assert np.array_equal(pol_a, pol_b.cpu().numpy())
-    assert np.allclose(rec_a, rec_b.cpu().numpy(), atol=1e-5)
+    run.lse = torch.logsumexp(s.masked_fill(mask, float("-inf")), dim=2).float().contiguous()
+    rep = H.compare(run)
+    _report("supplied row log-sum-exp", rep)
+    assert rep.units == 12 and len(rep.policies) >= 3
 
 
 def test_call_order_and_capacity_errors():
@@ -131,42 +138,60 @@ def test_call_order_and_capacity_errors():
 
 def test_llama7b_full_size_sampled_units():
     """BASELINE config 2 at full size (1024 units, n = 2048) in the launch configuration the
-    benchmark times; the oracle checks a seeded sample of units one by one."""
+    benchmark times; the oracle follows a seeded sample stratified over the planted patterns."""
     w = W["llama7b_b1"]            # the full decode horizon of the benchmark: 256 steps
     run = H.GpuRun(w, range(w.num_units))
-    rng = np.random.default_rng(5)
-    sample = sorted(rng.choice(w.num_units, size=16, replace=False).tolist())
+    sample = H.stratified_units(w, 4, seed=5)
     rep = H.compare(run, check_units=sample, state_steps=list(range(0, 256, 17)) + [255], check_rows=False,
                     probe_steps=[100, 200])
-    _report("llama7b_b1 full size, 16 sampled units, 256 steps", rep)
+    _report(f"llama7b_b1 full size, {len(sample)} units stratified over the planted patterns, 256 steps", rep)
+    _covers_realised_policies(rep, run.last_policy)
 
 
 # ---- the remaining BASELINE configurations at full size and over their whole decode horizon,
 # oracle on a seeded sample of units.
 
-def _full_size(name, n_sample, steps, T=None, state_steps=None, seed=0, probe_steps=()):
+def _full_size(name, per_pattern, steps, T=None, state_steps=None, seed=0, probe_steps=()):
     w = W[name].scaled(steps=steps) if T is None else W[name].scaled(steps=steps, T=T)
     run = H.GpuRun(w, range(w.num_units))
-    rng = np.random.default_rng(seed)
-    sample = sorted(rng.choice(w.num_units, size=n_sample, replace=False).tolist())
+    sample = H.stratified_units(w, per_pattern, seed)
     rep = H.compare(run, check_units=sample, state_steps=state_steps or [0, steps - 1], check_rows=False,
                     probe_steps=probe_steps)
-    _report(f"{name} full size (T={w.T}), {n_sample} sampled units, {steps} steps", rep)
+    _report(f"{name} full size (T={w.T}), {len(sample)} units stratified over the planted patterns, {steps} steps", rep)
+    _covers_realised_policies(rep, run.last_policy)
     return rep
 
 
-@pytest.mark.parametrize("T", [0.90, 0.98])
+@pytest.mark.parametrize("T", [0.90, 0.95, 0.98])
 def test_llama7b_b16_full_size_sampled_units(T):
-    _full_size("llama7b_b16", 12, 512, T=T, seed=16, state_steps=[0, 1, 63, 255, 511])
+    _full_size("llama7b_b16", 2, 512, T=T, seed=16, state_steps=[0, 1, 63, 255, 511], probe_steps=[300])
 
 
 def test_llama13b_b4_full_size_sampled_units():
-    _full_size("llama13b_b4", 6, 512, seed=13, state_steps=[0, 31, 255, 511])
+    _full_size("llama13b_b4", 2, 512, seed=13, state_steps=[0, 31, 255, 511], probe_steps=[2, 400])
 
 
 def test_llama65b_b2_full_size_sampled_units():
-    # two probed steps: units above 6144 held tokens take the update kernel's large-unit path
-    _full_size("llama65b_b2", 4, 1024, seed=65, probe_steps=[1, 500], state_steps=[0, 15, 511, 1023])
+    # two units of every planted pattern, the full-cache (broad) ones included; two probed steps
+    # (a probed step runs the score update and the top-k selection on every unit, so the
+    # full-cache units take the update kernel's large-unit path with more than 8192 tokens)
+    rep = _full_size("llama65b_b2", 2, 1024, seed=65, probe_steps=[1, 500], state_steps=[0, 15, 511, 1023])
+    assert rep.policies.get(4, 0) >= 2
+
+
+# The update kernel keeps a unit's scores in registers up to 6144 held tokens; above that it
+# works from memory (score update, uncached top-k selection, two-scan hole / mover lists,
+# deferred bookkeeping moves). Forced policies with budgets that hold more than 6144 tokens of
+# a 6400-token prompt drive that path with evictions at every step.
+@pytest.mark.parametrize("policy,r_f,r_l", [(2, 0.97, 0.3), (3, 0.9, 0.08)])
+def test_update_path_of_units_above_6144_tokens(policy, r_f, r_l):
+    w = W["llama7b_b1"].scaled(name="large_unit", layers=1, heads=5, batch=1, prompt_len=6400, steps=40,
+                               r_f=r_f, r_l=r_l, seed=6400 + policy)
+    run = H.GpuRun(w, range(w.num_units), forced_policy=policy)
+    rep = H.compare(run, check_rows=False)
+    _report(f"update path above 6144 held tokens: forced policy {policy}, r_f={r_f}, r_l={r_l}", rep)
+    lens = run.fg.fastgen_export_state(lengths_only=True)["lengths"].cpu().numpy()
+    assert lens.min() > 6144, lens
 
 
 @pytest.mark.parametrize("kw", [
@@ -290,7 +315,7 @@ def _random_case(seed):
         n=int(rng.choice([1, 2, 7, 31, 32, 33, 63, 64, 65, 100, 129, 255, 256, 257, 300])),
         S=int(rng.choice([0, 1, 3, 17, 40, 70])),
         d=int(rng.choice([64, 128])), dtype=str(rng.choice(["bf16", "f32"])),
-        T=float(rng.choice([0.5, 0.8, 0.9, 0.95, 0.99, 1.0])),
+        T=float(rng.choice([0.5, 0.8, 0.9, 0.95, 0.99, 0.999])),
         r_l=float(rng.choice([0.0, 0.05, 0.3, 0.7, 1.0])), r_f=float(rng.choice([0.0, 0.05, 0.3, 0.7, 1.0])),
         heads=int(rng.integers(1, 8)), batch=int(rng.integers(1, 4)), G=int(rng.choice([1, 1, 2, 3])),
         family=families[int(rng.integers(0, len(families)))], forced=int(rng.choice([-1, -1, -1, 4])))
@@ -308,3 +333,4 @@ def test_random_small_configurations(seed):
     probe = [s for s in (0, c["S"] // 2) if s < c["S"]]
     rep = H.compare(run, probe_steps=probe)
     _report(f"random {seed} {c}", rep)
+    assert rep.margin_excluded < rep.units          # the case must compare something discrete
