@@ -109,6 +109,21 @@ fg_status fastgen_create(const fg_config* cfg, void* workspace, size_t bytes, fa
 /* Releases the host-side context. The workspace stays the caller's. NULL is accepted. */
 fg_status fastgen_destroy(fastgen_ctx* ctx);
 
+/* Token classes from token ids (Sec. 3.4: C_special keeps the special tokens such as the
+ * begin-of-sentence or instruction markers, C_punct. the punctuation tokens): writes, for every
+ * token, FG_CLASS_SPECIAL if its id is in special_ids, FG_CLASS_PUNCT if it is in punct_ids
+ * (both bits if in both, 0 otherwise). Usable for the prompt ([B, n] ids -> token_class of
+ * fastgen_profile) and for each decode step ([B] ids -> class_new).
+ *   token_ids    device [count] int32.
+ *   special_ids, punct_ids   HOST arrays of num_special / num_punct ids, at most 64 entries
+ *                each (they travel as kernel arguments); NULL is accepted with a count of 0.
+ *   token_class  device [count] uint8, written.
+ * Stateless: needs no context. FG_EINVAL for null device pointers with count > 0, negative
+ * counts or lists longer than 64; count == 0 launches nothing. */
+fg_status fastgen_classify(const int32_t* token_ids, int64_t count, const int32_t* special_ids,
+                           int32_t num_special, const int32_t* punct_ids, int32_t num_punct,
+                           uint8_t* token_class, void* stream);
+
 /* Stage 1a -- attention profiling and policy choice (Alg. 1, Sec. 3.3 Eq. 1, Sec. 3.4 Eq. 2).
  *   Q, K         device [U (Q: U * G), n, d] in cfg.dtype, 16-byte aligned: the prompt's
  *                queries/keys.

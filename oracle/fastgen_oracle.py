@@ -82,6 +82,22 @@ def frequent_budget(r_f: float, L: int) -> int:
 
 
 # ----------------------------------------------------------------------------------------
+# Sec. 3.4: which tokens C_special and C_punct. keep
+# ----------------------------------------------------------------------------------------
+
+def classify_tokens(token_ids, special_ids, punct_ids) -> np.ndarray:
+    """Class byte of every token: bit 0 if the token is a special token (e.g. the
+    begin-of-sentence or instruction markers), bit 1 if it is a punctuation token."""
+    ids = np.asarray(token_ids)
+    special, punct = set(int(x) for x in special_ids), set(int(x) for x in punct_ids)
+    out = np.zeros(ids.shape, dtype=np.uint8)
+    for idx in np.ndindex(ids.shape):
+        t = int(ids[idx])
+        out[idx] = (CLASS_SPECIAL if t in special else 0) | (CLASS_PUNCT if t in punct else 0)
+    return out
+
+
+# ----------------------------------------------------------------------------------------
 # Alg. 1, line "A <- softmax(Q K^T)"
 # ----------------------------------------------------------------------------------------
 

@@ -23,7 +23,7 @@ STATUS_NAMES = ("FG_OK", "FG_EINVAL", "FG_ENOMEM", "FG_EHIP", "FG_ESTATE", "FG_E
 EXPORTED = (
     "fastgen_workspace_bytes", "fastgen_create", "fastgen_destroy", "fastgen_profile",
     "fastgen_compact", "fastgen_decode_step", "fastgen_decode_step_probe", "fastgen_export_state", "fastgen_last_error",
-    "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing", "fastgen_profile_static",
+    "fastgen_version", "fastgen_enable_timing", "fastgen_read_timing", "fastgen_profile_static", "fastgen_classify",
 )
 PHASES = ("sweep1", "sweep2", "select", "compact", "decode_attn", "decode_update")
 
@@ -65,6 +65,9 @@ def load_library() -> ctypes.CDLL:
     lib.fastgen_profile.argtypes = [vp] * 9
     lib.fastgen_profile_static.restype = ctypes.c_int
     lib.fastgen_profile_static.argtypes = [cp] + [vp] * 8
+    lib.fastgen_classify.restype = ctypes.c_int
+    lib.fastgen_classify.argtypes = [vp, ctypes.c_int64, ctypes.POINTER(ctypes.c_int32), ctypes.c_int32,
+                                     ctypes.POINTER(ctypes.c_int32), ctypes.c_int32, vp, vp]
     lib.fastgen_compact.restype = ctypes.c_int
     lib.fastgen_compact.argtypes = [vp] * 4
     lib.fastgen_decode_step.restype = ctypes.c_int
@@ -109,6 +112,23 @@ def make_config(num_units: int, num_seqs: int, head_dim: int, dtype: torch.dtype
 
 def fastgen_workspace_bytes(cfg: FgConfig) -> int:
     return int(load_library().fastgen_workspace_bytes(ctypes.byref(cfg)))
+
+
+def fastgen_classify(token_ids: torch.Tensor, special_ids, punct_ids,
+                     token_class: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Class bytes (FG_CLASS_* bits) of int32 token ids on the device; the id lists are host
+    sequences of at most 64 ids each."""
+    lib = load_library()
+    assert token_ids.dtype == torch.int32
+    if token_class is None:
+        token_class = torch.empty(token_ids.shape, dtype=torch.uint8, device=token_ids.device)
+    sp = (ctypes.c_int32 * max(1, len(special_ids)))(*[int(x) for x in special_ids])
+    pu = (ctypes.c_int32 * max(1, len(punct_ids)))(*[int(x) for x in punct_ids])
+    st = lib.fastgen_classify(_ptr(token_ids), token_ids.numel(), sp, len(special_ids), pu, len(punct_ids),
+                              _ptr(token_class), _stream())
+    if st != FG_OK:
+        raise FastGenError(st, lib.fastgen_last_error(None).decode())
+    return token_class
 
 
 def fastgen_profile_static(cfg: FgConfig, Q: torch.Tensor, K: torch.Tensor, token_class: torch.Tensor,

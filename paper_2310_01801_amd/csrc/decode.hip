@@ -59,10 +59,13 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   const int n_items = a.chunk_off[a.U];
   const int overflow = a.flags[0];
   const int4 rec = *reinterpret_cast<const int4*>(a.item_unit + (size_t)item * 8);
-  const int2 rec_off = *reinterpret_cast<const int2*>(a.item_unit + (size_t)item * 8 + 4);
+  const int4 rec_off = *reinterpret_cast<const int4*>(a.item_unit + (size_t)item * 8 + 4);
   if (overflow != 0 || item >= n_items) return;
   const int u = rec.x, chunk = rec.y;
   const int Lold = rec.w, L = Lold + 1;
+  // the logits are kept only where the update kernel needs them: policies with `frequent`
+  // (cumulative scores), or every unit when the step is probed
+  const bool keep_logits = ((rec_off.z >> 8) & FG_COMP_FREQUENT) != 0 || a.probe != nullptr;
   const int start = chunk * CH;
   if (start >= L) return;
   if (L > rec.z) {  // cannot happen while the host bounds the step count
@@ -74,6 +77,11 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane % LPR, sub = lane / LPR;
   const float c = a.scale * FG_LOG2E;
+  // Score path (Sec. 3.4, cumulative attention score): the products of two bf16 (or float32)
+  // inputs are exact in float64 and 128 of them add up to ~1e-16 there, so the logit that the
+  // update kernel turns into this step's attention is the oracle's to the last bits; the
+  // float32 logit (good to ~1e-7 of its size) serves the output only.
+  const double c_d = (double)a.scale * 1.4426950408889634074;
 
   const char* ck = static_cast<const char*>(a.ck);
   const char* cv = static_cast<const char*>(a.cv);
@@ -154,14 +162,22 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
       for (int it = 0; it < ITERS; ++it) {
         float kf[EPL];
         fg_unpack<ESIZE>(kv[it], kf);
-        float dot = 0.f;
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
-        dot = fg_group_sum<LPR>(dot);
         const int tok = wave * TPW + it * TPL + sub;
         const bool ok = tok < cnt;
-        x[it] = ok ? dot * c : FG_NEG_BIG;
-        if (ok && g == 0) a.clogit[(off + start + tok) * G + h] = x[it];
+        if (keep_logits) {
+          double dd = 0.0;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dd = fma((double)qv[e], (double)kf[e], dd);
+          dd = fg_group_sum_f64<LPR>(dd) * c_d;
+          if (ok && g == 0) a.clogit[(off + start + tok) * G + h] = dd;
+          x[it] = ok ? (float)dd : FG_NEG_BIG;
+        } else {
+          float dot = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+          dot = fg_group_sum<LPR>(dot);
+          x[it] = ok ? dot * c : FG_NEG_BIG;
+        }
         mw = fmaxf(mw, x[it]);
       }
       mw = fg_wave_max(mw);
@@ -217,14 +233,22 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   for (int it = 0; it < ITERS; ++it) {
     float kf[EPL];
     fg_unpack<ESIZE>(kv[it], kf);
-    float dot = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
-    dot = fg_group_sum<LPR>(dot);
     const int tok = wave * TPW + it * TPL + sub;
     const bool ok = tok < cnt;
-    x[it] = ok ? dot * c : FG_NEG_BIG;
-    if (ok && g == 0) a.clogit[off + start + tok] = x[it];
+    if (keep_logits) {   // wave-uniform
+      double dd = 0.0;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) dd = fma((double)qv[e], (double)kf[e], dd);
+      dd = fg_group_sum_f64<LPR>(dd) * c_d;
+      if (ok && g == 0) a.clogit[off + start + tok] = dd;
+      x[it] = ok ? (float)dd : FG_NEG_BIG;
+    } else {
+      float dot = 0.f;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+      dot = fg_group_sum<LPR>(dot);
+      x[it] = ok ? dot * c : FG_NEG_BIG;
+    }
     mx = fmaxf(mx, x[it]);
   }
   mx = fg_wave_max(mx);
@@ -284,7 +308,7 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   __shared__ fg_select_smem sm;
   __shared__ int ired[20];
   __shared__ double dred[8];
-  __shared__ float s_M[16], s_inv[16];  // per query head: merged max and 1 / sum
+  __shared__ float s_M[16];  // per query head: merged maximum of the scaled logits
   const int u = blockIdx.x, tid = threadIdx.x;
   const int G = GRP ? a.G : 1;
   // independent header loads first, then the checks
@@ -309,7 +333,7 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
 
   // ---- merge the chunk partials of every query head:
   //      o = sum_c o_c 2^(M_c - M) / sum_c l_c 2^(M_c - M)
-  float M = FG_NEG_BIG, inv = 0.f;   // of head 0 (the only one without grouping)
+  float M = FG_NEG_BIG;   // of head 0 (the only one without grouping)
   for (int h = 0; h < G; ++h) {
     const float* ph = part + (size_t)h * (D + 2);
     const size_t cs = (size_t)G * (D + 2);  // stride between chunks
@@ -331,19 +355,31 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
       for (int cix = 0; cix < nch; ++cix) o += ph[cix * cs + 2 + tid] * fg_exp2(ph[cix * cs] - Mh);
       fg_store_out<ESIZE>(a.out, ((size_t)u * G + h) * D + tid, o * invh);
     }
-    if (h == 0) { M = Mh; inv = invh; }
-    if (GRP && tid == 0) { s_M[h] = Mh; s_inv[h] = invh; }
+    if (h == 0) M = Mh;
+    if (GRP && tid == 0) s_M[h] = Mh;
   }
-  // Grouped heads: this step's attention on held slot j summed over the query heads (what the
-  // token's cumulative score receives) replaces head 0's logit in place, so that the rest of
-  // the kernel reads one ready value per slot (each thread only touches its own slots).
+  // Score path in float64 (Sec. 3.4, cumulative attention score): this step's attention on held
+  // slot j is a_j = 2^(x_j - M) / Z with the float64 logits x_j the attention kernel kept and
+  // Z = sum_j 2^(x_j - M) summed here in float64 (M is only a shift: the merged float maximum).
+  // Grouped heads: a_j summed over the query heads replaces head 0's logit in place, so that
+  // the rest of the kernel reads one ready value per slot (each thread only touches its own slots).
+  double inv_d = 0.0;   // 1 / Z of head 0 (the only one without grouping), set below where needed
   if (GRP) {
+    __shared__ double s_invd[16];
     __syncthreads();
     if (scored) {
+      for (int h = 0; h < G; ++h) {
+        const double Mh = (double)s_M[h];
+        double z = 0.0;
+        for (int j = tid; j < L; j += 256) z += exp2(a.clogit[(off + j) * G + h] - Mh);
+        z = fg_block_sum_f64(z, dred);
+        if (tid == 0) s_invd[h] = 1.0 / z;
+      }
+      __syncthreads();
       for (int j = tid; j < L; j += 256) {
-        float* lgj = a.clogit + (off + j) * G;
-        float sum = 0.f;
-        for (int h = 0; h < G; ++h) sum += fg_exp2(lgj[h] - s_M[h]) * s_inv[h];
+        double* lgj = a.clogit + (off + j) * G;
+        double sum = 0.0;
+        for (int h = 0; h < G; ++h) sum += exp2(lgj[h] - (double)s_M[h]) * s_invd[h];
         lgj[0] = sum;
       }
     }
@@ -373,13 +409,13 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   tk.mode = 0; tk.thr = 0; tk.pthr = 0;
   if (small) {
     // all loads first (they are independent), then the arithmetic, then the stores
-    float lg[NC];
+    double lg[NC];
     double sc[NC];
 #pragma unroll
     for (int i = 0; i < NC; ++i) {
       const int j = tid + 256 * i;
       kc[i] = 0;
-      lg[i] = 0.f;
+      lg[i] = 0.0;
       sc[i] = 0.0;
       if (j < L) {
         const int cb = cls[j];
@@ -392,15 +428,25 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
       }
     }
     if (scored) {
+      if (!GRP) {
+        // 2^(x_j - M) in place of the logits, their float64 sum over the workgroup
+        double z = 0.0;
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+          const int j = tid + 256 * i;
+          if (j < L) {
+            lg[i] = exp2(lg[i] - (double)M);
+            z += lg[i];
+          }
+        }
+        inv_d = 1.0 / fg_block_sum_f64(z, dred);
+      }
 #pragma unroll
       for (int i = 0; i < NC; ++i) {
         const int j = tid + 256 * i;
         if (j < L) {
           // cumulative attention score += this step's attention (Sec. 3.4, frequency policy)
-          float aj = lg[i];
-          if (GRP) asm volatile("" : "+v"(aj));  // (keeps the compiler from fusing the 24 updates: it spills otherwise)
-          else aj = fg_exp2(aj - M) * inv;
-          const double v = sc[i] + (double)aj;
+          const double v = sc[i] + (GRP ? lg[i] : lg[i] * inv_d);
           score[j] = v;
           kc[i] = (uint64_t)__double_as_longlong(v);
         }
@@ -417,9 +463,14 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
                                      [&](int j) { return (uint32_t)pos[j]; }, L, k_f, &sm);
     }
   } else if (scored) {
+    if (!GRP) {
+      double z = 0.0;
+      for (int j = tid; j < L; j += 256) z += exp2(a.clogit[off + j] - (double)M);
+      inv_d = 1.0 / fg_block_sum_f64(z, dred);
+    }
     for (int j = tid; j < L; j += 256) {
-      const float aj = GRP ? a.clogit[(off + j) * G] : fg_exp2(a.clogit[off + j] - M) * inv;
-      score[j] += (double)aj;
+      const double aj = GRP ? a.clogit[(off + j) * G] : exp2(a.clogit[off + j] - (double)M) * inv_d;
+      score[j] += aj;
     }
     __syncthreads();
     const int k_f = fg_budget(a.r_f, p_new + 1);
@@ -431,8 +482,8 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
     double r[5] = {0.0, 0.0, 0.0, 0.0, 0.0};
     for (int j = tid; j < L; j += 256) {
       // the mean of the G heads' rows
-      const double aj = GRP ? (double)a.clogit[(off + j) * G] / (double)G
-                            : (double)(fg_exp2(a.clogit[off + j] - M) * inv);
+      const double aj = GRP ? a.clogit[(off + j) * G] / (double)G
+                            : exp2(a.clogit[off + j] - (double)M) * inv_d;
       const int c = cls[j];
       const bool top = fg_in_topk(tk, score[j], (uint32_t)pos[j]), recent = pos[j] > p_new - a.w;
 #pragma unroll
@@ -486,7 +537,7 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   }
 
   // ---- in-place release: i-th hole (evicted slot below new_len) <- i-th kept slot above it
-  int* scratch = reinterpret_cast<int*>(a.clogit + off * G);  // logits are dead from here on
+  int* scratch = reinterpret_cast<int*>(a.clogit + off * G);  // logits are dead from here on (cap ints fit in cap doubles)
   __shared__ int s_move[2 * FG_MOVE_LDS];
   bool in_lds = false;
   __syncthreads();

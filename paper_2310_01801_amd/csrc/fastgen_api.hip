@@ -89,7 +89,7 @@ size_t layout_profile_part(const fg_config& c, fg_layout& L) {
   const size_t U = (size_t)c.num_units, n = (size_t)c.prompt_len;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-  L.lse2 = take(U * G * n * 4);
+  L.rowstat = take(U * G * n * 8);
   L.colsum = take(U * n * 8);
   L.bandcol = take(U * n * 8);
   L.keep = take(U * n);
@@ -121,7 +121,7 @@ fg_layout make_layout(const fg_config& c) {
   L.cscore = take(pool * 8);
   L.cpos = take(pool * 4);
   L.ccls = take(pool);
-  L.clogit = take(pool * G * 4);
+  L.clogit = take(pool * G * 8);
   L.chunk_off = take((U + 1) * 4);
   L.item_unit = take((size_t)L.max_chunks * 32);
   L.part = take((size_t)L.max_chunks * G * (d + 2) * 4);
@@ -194,7 +194,7 @@ hipError_t launch_profile_path(const fg_config& c, const fg_layout& L, char* ws,
   auto at = [&](size_t off) { return ws + off; };
   fg_profile_args pa;
   pa.Q = Q; pa.K = K;
-  pa.lse2 = reinterpret_cast<float*>(at(L.lse2));
+  pa.rowstat = reinterpret_cast<float2*>(at(L.rowstat));
   pa.colsum = reinterpret_cast<double*>(at(L.colsum));
   pa.bandcol = reinterpret_cast<double*>(at(L.bandcol));
   pa.U = c.num_units; pa.n = c.prompt_len; pa.d = c.head_dim; pa.w = w; pa.G = group_of(c);
@@ -202,7 +202,7 @@ hipError_t launch_profile_path(const fg_config& c, const fg_layout& L, char* ws,
   hipError_t e;
   *where = "fastgen_profile(row log-sum-exp sweep)";
   tm.begin(FG_PHASE_SWEEP1);
-  if (lse_opt) e = fg_launch_lse_to_log2(lse_opt, pa.lse2, (size_t)c.num_units * pa.G * c.prompt_len, s);
+  if (lse_opt) e = fg_launch_lse_to_rowstat(lse_opt, pa.rowstat, (size_t)c.num_units * pa.G * c.prompt_len, s);
   else e = (c.dtype == FG_BF16) ? fg_launch_profile_bf16(pa, 1, s) : fg_launch_profile_f32(pa, 1, s);
   tm.end();
   if (e != hipSuccess) return e;
@@ -303,6 +303,27 @@ fg_status fastgen_read_timing(fastgen_ctx* ctx, double* ms, int64_t* launches) {
   return st;
 }
 
+fg_status fastgen_classify(const int32_t* token_ids, int64_t count, const int32_t* special_ids,
+                           int32_t num_special, const int32_t* punct_ids, int32_t num_punct,
+                           uint8_t* token_class, void* stream) {
+  if (count < 0 || count > ((int64_t)1 << 38)) return sfail(FG_EINVAL, "fastgen_classify: count out of range");
+  if (num_special < 0 || num_special > FG_MAX_CLASS_IDS || num_punct < 0 || num_punct > FG_MAX_CLASS_IDS)
+    return sfail(FG_EINVAL, "fastgen_classify: an id list holds at most %d entries", FG_MAX_CLASS_IDS);
+  if ((num_special > 0 && !special_ids) || (num_punct > 0 && !punct_ids))
+    return sfail(FG_EINVAL, "fastgen_classify: an id list is NULL but its count is not 0");
+  if (count == 0) return FG_OK;
+  if (!token_ids || !token_class) return sfail(FG_EINVAL, "fastgen_classify: token_ids and token_class are required");
+  fg_classify_args a;
+  memset(&a, 0, sizeof(a));
+  a.token_ids = token_ids; a.token_class = token_class; a.count = count;
+  a.num_special = num_special; a.num_punct = num_punct;
+  for (int i = 0; i < num_special; ++i) a.special[i] = special_ids[i];
+  for (int i = 0; i < num_punct; ++i) a.punct[i] = punct_ids[i];
+  const hipError_t e = fg_launch_classify(a, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return sfail(FG_EHIP, "fastgen_classify: %s", hipGetErrorString(e));
+  return FG_OK;
+}
+
 fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K, const uint8_t* token_class,
                           const float* lse_opt, int32_t* policy, double* recovery,
                           int32_t* kept_count, void* stream) {
@@ -371,8 +392,8 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   const fg_layout& L = ctx->lay;
   PhaseChain tm(ctx, s, ctx->timing != 0);
   tm.begin(FG_PHASE_COMPACT);
-  hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int32_t>(ctx, L.len), at<int64_t>(ctx, L.off),
-                                   at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
+  hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int32_t>(ctx, L.len), at<int32_t>(ctx, L.policy),
+                                   at<int64_t>(ctx, L.off), at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
                                    at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
                                    L.max_chunks, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(offsets)");
@@ -417,7 +438,7 @@ static fg_status decode_step_impl(fastgen_ctx* ctx, const void* q, const void* k
   da.flags = at<int32_t>(ctx, L.flags);
   da.ck = at<void>(ctx, L.ck); da.cv = at<void>(ctx, L.cv);
   da.cscore = at<double>(ctx, L.cscore); da.cpos = at<int32_t>(ctx, L.cpos);
-  da.ccls = at<uint8_t>(ctx, L.ccls); da.clogit = at<float>(ctx, L.clogit);
+  da.ccls = at<uint8_t>(ctx, L.ccls); da.clogit = at<double>(ctx, L.clogit);
   da.chunk_off = at<int32_t>(ctx, L.chunk_off); da.item_unit = at<int32_t>(ctx, L.item_unit);
   da.part = at<float>(ctx, L.part);
   da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;

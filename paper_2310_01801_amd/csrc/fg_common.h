@@ -91,6 +91,19 @@ template <int CTRL>
 __device__ __forceinline__ double fg_dpp_f64(double v) {
   return __hiloint2double(fg_dpp_i32<CTRL>(__double2hiint(v)), fg_dpp_i32<CTRL>(__double2loint(v)));
 }
+// Sum of a double over aligned groups of N consecutive lanes (N <= 32); every lane of the group
+// receives the total. Fixed order.
+template <int N>
+__device__ __forceinline__ double fg_group_sum_f64(double v) {
+  static_assert(N <= 32, "groups of up to 32 lanes");
+  if (N >= 2) v += fg_dpp_f64<FG_DPP_XOR1>(v);
+  if (N >= 4) v += fg_dpp_f64<FG_DPP_XOR2>(v);
+  if (N >= 8) v += fg_dpp_f64<FG_DPP_HALF_MIRROR>(v);
+  if (N >= 16) v += fg_dpp_f64<FG_DPP_MIRROR>(v);
+  if (N >= 32) v += fg_shfl_xor_f64(v, 16);
+  return v;
+}
+
 __device__ __forceinline__ double fg_wave_sum_f64(double v) {
   v += fg_dpp_f64<FG_DPP_XOR1>(v);
   v += fg_dpp_f64<FG_DPP_XOR2>(v);

@@ -13,7 +13,8 @@
 // Every region starts on a 256-byte boundary. Offsets are in bytes from the workspace base.
 struct fg_layout {
   // profiling scratch
-  size_t lse2;      // [U * G, n] float   row log2-sum-exp2 of the scaled logits, per query head
+  size_t rowstat;   // [U * G, n] float2  per query row (m, 1/l): softmax row = 2^(c q.k - m) / l, with m a
+                    //                    shift at or near the row's largest scaled logit (log2 domain)
   size_t colsum;    // [U, n] double  cumulative attention score of every prompt token
   size_t bandcol;   // [U, n] double  the part of colsum inside the local band
   size_t keep;      // [U, n] uint8   0 = dropped, else 4 | class bits of the kept token
@@ -32,10 +33,11 @@ struct fg_layout {
   size_t cscore;    // [pool] double
   size_t cpos;      // [pool] int32
   size_t ccls;      // [pool] uint8
-  size_t clogit;    // [pool, G] float   this step's scaled logit of every held token, per query head
+  size_t clogit;    // [pool, G] double  this step's scaled logit of every held token, per query head (written
+                    //                   for the units whose cumulative scores are kept)
   // decode scratch
   size_t chunk_off; // [U + 1] int32  first chunk of each unit in the flat work list
-  size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, tokens held, pool offset lo/hi, 0, 0
+  size_t item_unit; // [max_chunks, 8] int32  work-item records: unit, chunk, cap, tokens held, pool offset lo/hi, policy word, 0
   size_t part;      // [max_chunks, G, d + 2] float  split-KV partial (max, sum, o) per query head
   size_t total;
   int64_t pool_tokens;
@@ -66,9 +68,9 @@ constexpr int FG_DECODE_CHUNK = 256;  // tokens per split-KV work item
 // ---------------------------------------------------------------- launch arguments
 struct fg_profile_args {
   const void* Q; const void* K;
-  float* lse2; double* colsum; double* bandcol;
+  float2* rowstat; double* colsum; double* bandcol;
   int U, n, d, w;
-  int G;  // query heads per K/V unit: Q and lse2 hold U * G units
+  int G;  // query heads per K/V unit: Q and rowstat hold U * G units
   float scale;
 };
 
@@ -95,7 +97,7 @@ struct fg_compact_args {
 struct fg_decode_args {
   const void* q; const void* k_new; const void* v_new; const uint8_t* class_new; void* out;
   const int32_t* policy; const int32_t* cap; const int64_t* off; int32_t* len; int32_t* flags;
-  void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; float* clogit;
+  void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls; double* clogit;
   const int32_t* chunk_off; int32_t* item_unit; float* part;
   int U, n, d, dtype, units_per_seq, w, step, G;
   int family[4];   // FG_COMP_* mask of policy ids 0..3 (stability probe)
@@ -115,12 +117,19 @@ struct fg_export_args {
 
 hipError_t fg_launch_profile_bf16(const fg_profile_args&, int pass, hipStream_t);
 hipError_t fg_launch_profile_f32(const fg_profile_args&, int pass, hipStream_t);
-hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t);
+hipError_t fg_launch_lse_to_rowstat(const float* lse_nat, float2* rowstat, size_t count, hipStream_t);
+constexpr int FG_MAX_CLASS_IDS = 64;  // ids per list of fastgen_classify (passed by value)
+struct fg_classify_args {
+  const int32_t* token_ids; uint8_t* token_class; long long count;
+  int num_special, num_punct;
+  int32_t special[FG_MAX_CLASS_IDS], punct[FG_MAX_CLASS_IDS];
+};
+hipError_t fg_launch_classify(const fg_classify_args&, hipStream_t);
 hipError_t fg_launch_select(const fg_select_args&, hipStream_t);
 hipError_t fg_launch_compact(const fg_compact_args&, hipStream_t);
-hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, int64_t* off, int32_t* chunk_off, int32_t* item_unit,
-                             int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
-                             hipStream_t);
+hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, const int32_t* policy, int64_t* off,
+                             int32_t* chunk_off, int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens,
+                             int64_t max_chunks, hipStream_t);
 hipError_t fg_launch_decode_attn(const fg_decode_args&, hipStream_t);
 hipError_t fg_launch_decode_update(const fg_decode_args&, hipStream_t);
 hipError_t fg_launch_export(const fg_export_args&, hipStream_t);

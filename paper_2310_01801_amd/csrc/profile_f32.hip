@@ -12,11 +12,11 @@ constexpr int kTile = 32;
 
 template <int D, int PASS>
 __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
-    const float* __restrict__ Q, const float* __restrict__ K, float* __restrict__ lse2,
+    const float* __restrict__ Q, const float* __restrict__ K, float2* __restrict__ rowstat,
     double* __restrict__ colsum, double* __restrict__ bandcol, int n, int w, float c, int nblk,
     int G) {
   __shared__ __attribute__((aligned(16))) float tile[kTile][D];
-  __shared__ float lse_t[kTile];
+  __shared__ float2 stat_t[kTile];
 
   const int unit = blockIdx.x / nblk, tid = threadIdx.x;
   const int WG0 = (blockIdx.x % nblk) * 256;
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
   const size_t mat = (size_t)n * D;
   const float* own_mat = (PASS == 1 ? Q : K) + (size_t)unit * mat;
   const float* str_base = (PASS == 1) ? K + (size_t)(unit / G) * mat : Q + (size_t)unit * G * mat;
-  const float* lse_base = lse2 + (size_t)unit * (PASS == 1 ? 1 : G) * n;
+  const float2* stat_base = rowstat + (size_t)unit * (PASS == 1 ? 1 : G) * n;
 
   float o[D];
 #pragma unroll
@@ -46,7 +46,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
   const int heads = (PASS == 1) ? 1 : G;
   for (int h = 0; h < heads; ++h) {
   const float* str_mat = str_base + (size_t)h * mat;
-  const float* lse_row = lse_base + (size_t)h * n;
+  const float2* stat_row = stat_base + (size_t)h * n;
   for (int t = t_begin; t < t_end; ++t) {
     const int t0 = t * kTile;
     __syncthreads();
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
       if (t0 + item < n) v = *reinterpret_cast<const f32x4*>(str_mat + (size_t)(t0 + item) * D + ch * 4);
       *reinterpret_cast<f32x4*>(&tile[item][ch * 4]) = v;
     }
-    if (PASS == 2 && tid < kTile) lse_t[tid] = (t0 + tid < n) ? lse_row[t0 + tid] : 0.f;
+    if (PASS == 2 && tid < kTile) stat_t[tid] = (t0 + tid < n) ? stat_row[t0 + tid] : make_float2(0.f, 0.f);
     __syncthreads();
     if (own >= n) continue;
     for (int it = 0; it < kTile; ++it) {
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
         l_run = l_run * (double)fg_exp2(m_run - m_new) + (double)fg_exp2(x - m_new);
         m_run = m_new;
       } else {
-        const float p = fg_exp2(x - lse_t[it]);
+        const float p = fg_exp2(x - stat_t[it].x) * stat_t[it].y;
         col_acc += (double)p;
         if (s_idx - own < w) band_acc += (double)p;
       }
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
   }
   }
   if (own < n) {
-    if (PASS == 1) lse2[(size_t)unit * n + own] = m_run + (float)log2(l_run);
+    if (PASS == 1) rowstat[(size_t)unit * n + own] = make_float2(m_run, (float)(1.0 / l_run));
     else {
       colsum[(size_t)unit * n + own] = col_acc;
       bandcol[(size_t)unit * n + own] = band_acc;
@@ -97,17 +97,23 @@ hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const float* Q = static_cast<const float*>(a.Q);
   const float* K = static_cast<const float*>(a.K);
   if (pass == 1)
-    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 1>), grid, block, 0, s, Q, K, a.rowstat, a.colsum,
                        a.bandcol, a.n, a.w, c, nblk, a.G);
   else
-    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+    hipLaunchKernelGGL((fg_profile_f32_kernel<D, 2>), grid, block, 0, s, Q, K, a.rowstat, a.colsum,
                        a.bandcol, a.n, a.w, c, nblk, a.G);
   return hipGetLastError();
 }
 
-__global__ void fg_lse_to_log2_kernel(const float* __restrict__ in, float* __restrict__ out, size_t count) {
+// A caller-supplied natural-log row log-sum-exp as (m, 1/l): m = the nearest integer to its
+// log2 value, 1/l = 2^(m - log2 value) in [0.70, 1.42], so that no bits are lost to the
+// magnitude of the log-sum-exp itself.
+__global__ void fg_lse_to_rowstat_kernel(const float* __restrict__ in, float2* __restrict__ out, size_t count) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < count) out[i] = in[i] * FG_LOG2E;
+  if (i >= count) return;
+  const double l2 = (double)in[i] * 1.4426950408889634074;
+  const double m = rint(l2);
+  out[i] = make_float2((float)m, (float)exp2(m - l2));
 }
 
 }  // namespace
@@ -117,8 +123,8 @@ hipError_t fg_launch_profile_f32(const fg_profile_args& a, int pass, hipStream_t
   return launch<64>(a, pass, s);
 }
 
-hipError_t fg_launch_lse_to_log2(const float* lse_nat, float* lse2, size_t count, hipStream_t s) {
+hipError_t fg_launch_lse_to_rowstat(const float* lse_nat, float2* rowstat, size_t count, hipStream_t s) {
   const unsigned blocks = (unsigned)((count + 255) / 256);
-  hipLaunchKernelGGL(fg_lse_to_log2_kernel, dim3(blocks), dim3(256), 0, s, lse_nat, lse2, count);
+  hipLaunchKernelGGL(fg_lse_to_rowstat_kernel, dim3(blocks), dim3(256), 0, s, lse_nat, rowstat, count);
   return hipGetLastError();
 }

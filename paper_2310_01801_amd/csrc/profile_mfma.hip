@@ -2,9 +2,14 @@
 // Sec. 3.4: cumulative attention score per token; Sec. 3.3 Eq. 1: recovery of a policy).
 //
 // The attention map is never stored. Two sweeps over the causal half of Q K^T:
-//   PASS 1  row log-sum-exp        lse2_i  = log2 sum_{j<=i} 2^(c * q_i.k_j),  c = scale*log2(e)
-//   PASS 2  column reductions      colsum_j  = sum_{i>=j}            2^(c * q_i.k_j - lse2_i)
+//   PASS 1  row statistics         m_i = max_{j<=i} c * q_i.k_j,   l_i = sum_{j<=i} 2^(c * q_i.k_j - m_i),
+//                                  c = scale*log2(e); stored as the pair (m_i, 1/l_i)
+//   PASS 2  column reductions      colsum_j  = sum_{i>=j}            2^(c * q_i.k_j - m_i) / l_i
 //                                  bandcol_j = sum_{i=j}^{j+w-1}     (same terms)
+// (The pair instead of one log-sum-exp value: a float holds m_i + log2 l_i, a number around
+// 10..30, only to about 2e-6, which would be a relative error of 1e-6 in every element of the
+// row; m_i is exact and 1/l_i is good to 6e-8. The shift costs nothing: the accumulation
+// s += p becomes one fused multiply-add s += p~ * (1/l_i).)
 // colsum is the "cumulative sum of attention score" of token j (frequent policy and every
 // static policy's recovery); bandcol is what the local policy recovers of column j.
 //
@@ -32,7 +37,7 @@ struct Lds {
 
 template <int D, int PASS>
 __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
-    const __bf16* __restrict__ Q, const __bf16* __restrict__ K, float* __restrict__ lse2,
+    const __bf16* __restrict__ Q, const __bf16* __restrict__ K, float2* __restrict__ rowstat,
     double* __restrict__ colsum, double* __restrict__ bandcol, int U, int n, int w, float c,
     int nblk, int G) {
   constexpr int KK = D / 16;
@@ -42,7 +47,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   static_assert(LOADS >= 1, "tile too small");
 
   __shared__ __attribute__((aligned(16))) unsigned char tile_lds[2][Lds<D>::kTileBytes];
-  __shared__ __attribute__((aligned(16))) float lse_lds[2][kTile];
+  __shared__ __attribute__((aligned(16))) float stat_lds[2][2][kTile];  // [buffer][m | 1/l][row]
 
   // ---- which (unit, owner block): units of one XCD walk one unit's blocks back to back
   const int idx = blockIdx.x;
@@ -68,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   const size_t mat = (size_t)n * D;
   const __bf16* own_mat = (PASS == 1 ? Q : K) + (size_t)unit * mat;
   const __bf16* str_mat = (PASS == 1) ? K + (size_t)(unit / G) * mat : Q + (size_t)unit * G * mat;
-  const float* lse_row = lse2 + (size_t)unit * (PASS == 1 ? 1 : G) * n;
+  const float2* stat_row = rowstat + (size_t)unit * (PASS == 1 ? 1 : G) * n;
   const int heads = (PASS == 1) ? 1 : G;
 
   const int WG0 = blk * kOwnPerBlock;       // first owner item of the workgroup
@@ -102,17 +107,17 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   // them is masked), so a load costs no vector-ALU instruction.
   const __amdgpu_buffer_rsrc_t str_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(str_mat), 0, heads * n * D * 2, 0x00020000);
-  const __amdgpu_buffer_rsrc_t lse_rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(lse_row), 0, heads * n * 4, 0x00020000);
+  const __amdgpu_buffer_rsrc_t stat_rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float2*>(stat_row), 0, heads * n * 8, 0x00020000);
   int voff[LOADS];
 #pragma unroll
   for (int r = 0; r < LOADS; ++r) {
     const int q = tid + 256 * r;
     voff[r] = (q / CHUNKS_PER_ROW) * (D * 2) + (q % CHUNKS_PER_ROW) * 16;
   }
-  const int voff_lse = (tid & (kTile - 1)) * 4;
+  const int voff_stat = (tid & (kTile - 1)) * 8;
   u32x4 stage[LOADS];
-  float stage_lse = 0.f;
+  float2 stage_stat = make_float2(0.f, 0.f);
   // `row0` = first streamed row of the tile counted over all heads (head * n + t * 32); a tile
   // that runs past its head's last row reads the next head's rows (or zeros after the last
   // head): those rows are masked wherever they are used.
@@ -120,7 +125,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 #pragma unroll
     for (int r = 0; r < LOADS; ++r)
       stage[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(str_rsrc, voff[r], row0 * (D * 2), 0));
-    if (PASS == 2) stage_lse = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(lse_rsrc, voff_lse, row0 * 4, 0));
+    if (PASS == 2) stage_stat = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(stat_rsrc, voff_stat, row0 * 8, 0));
   };
   auto lstore = [&](int buf) {
 #pragma unroll
@@ -129,11 +134,12 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
       const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
       *reinterpret_cast<u32x4*>(&tile_lds[buf][item * RS + ch * 16]) = stage[r];
     }
-    if (PASS == 2 && tid < kTile) lse_lds[buf][tid] = stage_lse;
+    if (PASS == 2 && tid < kTile) { stat_lds[buf][0][tid] = stage_stat.x; stat_lds[buf][1][tid] = stage_stat.y; }
   };
 
   // ---- per-lane running statistics
-  float m_run[2] = {FG_NEG_BIG, FG_NEG_BIG}, l_run[2] = {0.f, 0.f};  // pass 1
+  float m_run[2] = {FG_NEG_BIG, FG_NEG_BIG};                         // pass 1
+  double l_run[2] = {0.0, 0.0};
   double col_acc[2] = {0.0, 0.0}, band_acc[2] = {0.0, 0.0};          // pass 2
 
   // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards from the end,
@@ -199,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
             float s = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
-            l_run[f] = l_run[f] * fg_exp2(m_run[f] - m_new) + s;
+            l_run[f] = l_run[f] * (double)fg_exp2(m_run[f] - m_new) + (double)s;
             m_run[f] = m_new;
           } else {  // diagonal tile: causal mask col <= row
             const int lim = row - sbase;  // valid iff (i>>2)*8 + (i&3) <= lim
@@ -217,17 +223,19 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
               const float p = fg_exp2(fmaf(acc[f][i], c, -m_new));
               s += ok ? p : 0.f;
             }
-            l_run[f] = l_run[f] * fg_exp2(m_run[f] - m_new) + s;
+            l_run[f] = l_run[f] * (double)fg_exp2(m_run[f] - m_new) + (double)s;
             m_run[f] = m_new;
           }
         }
       } else {
-        // row log-sum-exps of the 16 streamed rows this lane sees
-        float ls[16];
+        // (m, 1/l) of the 16 streamed rows this lane sees
+        float ms[16], il[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(&lse_lds[buf][g * 8 + lh * 4]);
-          ls[g * 4 + 0] = v[0]; ls[g * 4 + 1] = v[1]; ls[g * 4 + 2] = v[2]; ls[g * 4 + 3] = v[3];
+          const f32x4 v = *reinterpret_cast<const f32x4*>(&stat_lds[buf][0][g * 8 + lh * 4]);
+          const f32x4 u = *reinterpret_cast<const f32x4*>(&stat_lds[buf][1][g * 8 + lh * 4]);
+          ms[g * 4 + 0] = v[0]; ms[g * 4 + 1] = v[1]; ms[g * 4 + 2] = v[2]; ms[g * 4 + 3] = v[3];
+          il[g * 4 + 0] = u[0]; il[g * 4 + 1] = u[1]; il[g * 4 + 2] = u[2]; il[g * 4 + 3] = u[3];
         }
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
@@ -240,7 +248,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
           if (full && (inside || outside)) {
             float s = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -ls[i]));
+            for (int i = 0; i < 16; ++i) s = fmaf(fg_exp2(fmaf(acc[f][i], c, -ms[i])), il[i], s);
             col_acc[f] += (double)s;
             if (inside) band_acc[f] += (double)s;  // the whole tile lies in the local band
           } else {
@@ -252,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
               const int o = (i >> 2) * 8 + (i & 3);
               const int dist = dbase + o;
               const bool ok = (dist >= 0) && (o < rlim);
-              const float p = fg_exp2(fmaf(acc[f][i], c, -ls[i]));
+              const float p = fg_exp2(fmaf(acc[f][i], c, -ms[i])) * il[i];
               s += ok ? p : 0.f;
               sb += (ok && dist < w) ? p : 0.f;
             }
@@ -274,11 +282,11 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
 #pragma unroll
     for (int f = 0; f < 2; ++f) {
       const float m_o = __shfl_xor(m_run[f], 32, 64);
-      const float l_o = __shfl_xor(l_run[f], 32, 64);
+      const double l_o = fg_shfl_xor_f64(l_run[f], 32);
       const float M = fmaxf(m_run[f], m_o);
-      const float L = l_run[f] * fg_exp2(m_run[f] - M) + l_o * fg_exp2(m_o - M);
+      const double L = l_run[f] * (double)fg_exp2(m_run[f] - M) + l_o * (double)fg_exp2(m_o - M);
       const int row = O0 + 32 * f + ln;
-      if (lh == 0 && row < n) lse2[(size_t)unit * n + row] = M + __log2f(L);
+      if (lh == 0 && row < n) rowstat[(size_t)unit * n + row] = make_float2(M, (float)(1.0 / L));
     }
   } else {
 #pragma unroll
@@ -306,10 +314,10 @@ hipError_t launch(const fg_profile_args& a, int pass, hipStream_t s) {
   const __bf16* Q = static_cast<const __bf16*>(a.Q);
   const __bf16* K = static_cast<const __bf16*>(a.K);
   if (pass == 1)
-    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 1>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 1>), grid, block, 0, s, Q, K, a.rowstat, a.colsum,
                        a.bandcol, units, a.n, a.w, c, nblk, a.G);
   else
-    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.lse2, a.colsum,
+    hipLaunchKernelGGL((fg_profile_mfma_kernel<D, 2>), grid, block, 0, s, Q, K, a.rowstat, a.colsum,
                        a.bandcol, units, a.n, a.w, c, nblk, a.G);
   return hipGetLastError();
 }

@@ -1,5 +1,6 @@
 // Policy choice and compaction (Alg. 1: "C <- apply Eq. 1 to A", "K^,V^ <- f(K,V,C)").
 //
+//   fg_classify_kernel token ids -> class bytes (special / punctuation).
 //   fg_select_kernel   per unit: the kept sets of the policy family (by default Eq. 2's:
 //                      special, +punctuation, +frequent, +local; "+" = union; any table of
 //                      component masks is accepted), their recoveries from the column /
@@ -14,6 +15,18 @@
 #include "fg_select.h"
 
 namespace {
+
+// Token ids -> class bytes (Sec. 3.4: which tokens C_special / C_punct. keep). The two id lists
+// are small and arrive by value; every thread compares its token with all of them.
+__global__ __launch_bounds__(256) void fg_classify_kernel(fg_classify_args a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.count) return;
+  const int32_t id = a.token_ids[i];
+  int c = 0;
+  for (int k = 0; k < a.num_special; ++k) c |= (id == a.special[k]) ? FG_CLASS_SPECIAL : 0;
+  for (int k = 0; k < a.num_punct; ++k) c |= (id == a.punct[k]) ? FG_CLASS_PUNCT : 0;
+  a.token_class[i] = (uint8_t)c;
+}
 
 __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
   __shared__ fg_select_smem sm;
@@ -172,11 +185,13 @@ __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restr
 
 // Work-item records of the decode attention kernel: item c of unit u covers slots
 // [256 * (c - chunk_off[u]), +256) of that unit. 8 ints per item: unit, chunk, cap, tokens held
-// by the unit (kept current by the update kernel), off lo, off hi, 0, 0.
+// by the unit (kept current by the update kernel), off lo, off hi, policy word (id | component
+// mask << 8), 0.
 __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restrict__ chunk_off,
                                                           const int32_t* __restrict__ cap,
                                                           const int64_t* __restrict__ off,
                                                           const int32_t* __restrict__ len,
+                                                          const int32_t* __restrict__ policy,
                                                           int32_t* __restrict__ item_rec,
                                                           const int32_t* __restrict__ flags, int U) {
   if (flags[0] != 0) return;
@@ -187,7 +202,7 @@ __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restr
   for (int c = c0; c < c1; ++c) {
     int32_t* r = item_rec + (size_t)c * 8;
     r[0] = u; r[1] = c - c0; r[2] = cap[u]; r[3] = len[u];
-    r[4] = (int32_t)(o & 0xffffffffll); r[5] = (int32_t)(o >> 32); r[6] = 0; r[7] = 0;
+    r[4] = (int32_t)(o & 0xffffffffll); r[5] = (int32_t)(o >> 32); r[6] = policy[u]; r[7] = 0;
   }
 }
 
@@ -304,6 +319,12 @@ __global__ __launch_bounds__(256) void fg_export_kernel(fg_export_args a, const 
 
 }  // namespace
 
+hipError_t fg_launch_classify(const fg_classify_args& a, hipStream_t s) {
+  const unsigned blocks = (unsigned)((a.count + 255) / 256);
+  hipLaunchKernelGGL(fg_classify_kernel, dim3(blocks), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t fg_launch_select(const fg_select_args& a, hipStream_t s) {
   hipLaunchKernelGGL(fg_select_kernel, dim3((unsigned)a.U), dim3(256), 0, s, a);
   return hipGetLastError();
@@ -315,13 +336,13 @@ hipError_t fg_launch_compact(const fg_compact_args& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, int64_t* off, int32_t* chunk_off,
-                             int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens, int64_t max_chunks,
-                             hipStream_t s) {
+hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, const int32_t* policy, int64_t* off,
+                             int32_t* chunk_off, int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens,
+                             int64_t max_chunks, hipStream_t s) {
   hipLaunchKernelGGL(fg_offsets_kernel, dim3(1), dim3(1024), 0, s, cap, off, chunk_off, flags, U,
                      pool_tokens, max_chunks);
   hipLaunchKernelGGL(fg_item_map_kernel, dim3((unsigned)((U + 255) / 256)), dim3(256), 0, s,
-                     chunk_off, cap, off, len, item_unit, flags, U);
+                     chunk_off, cap, off, len, policy, item_unit, flags, U);
   return hipGetLastError();
 }
 

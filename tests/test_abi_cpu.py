@@ -100,3 +100,16 @@ def test_static_profile_rejects_bad_arguments_on_the_host(lib):
     big = _cfg(num_units=1024, num_seqs=1, prompt_len=2048)
     assert call(ctypes.byref(big), fake, fake, fake, None, None, None, None, None) == binding.FG_ENOMEM
     assert b"static array holds 33554432" in lib.fastgen_last_error(None)
+
+
+def test_classify_rejects_bad_arguments_on_the_host(lib):
+    fake = 0x10000
+    ids = (ctypes.c_int32 * 70)(*range(70))
+    call = lib.fastgen_classify
+    assert call(None, 0, None, 0, None, 0, None, None) == binding.FG_OK            # nothing to do
+    assert call(None, 8, None, 0, None, 0, fake, None) == binding.FG_EINVAL
+    assert call(fake, 8, None, 0, None, 0, None, None) == binding.FG_EINVAL
+    assert call(fake, -1, None, 0, None, 0, fake, None) == binding.FG_EINVAL
+    assert call(fake, 8, ids, 65, None, 0, fake, None) == binding.FG_EINVAL        # more than 64 ids
+    assert b"at most 64" in lib.fastgen_last_error(None)
+    assert call(fake, 8, None, 3, None, 0, fake, None) == binding.FG_EINVAL        # a count without a list

@@ -642,3 +642,18 @@ def test_group_of_two_heads_rederived_by_loops(policy):
             keep |= {j for j in held if j > p - w}
         score = {j: s for j, s in score.items() if j in keep}
         assert list(res["states"][t]) == sorted(keep)
+
+
+# ---------------------------------------------------------------- token classes (Sec. 3.4)
+
+def test_classify_tokens_by_hand_and_against_set_membership():
+    ids = np.array([[0, 5, 7, 5, 9], [13, 0, 2, 7, 7]])
+    got = fo.classify_tokens(ids, special_ids=[0, 7], punct_ids=[5, 7, 13])
+    # 0 -> special; 5, 13 -> punctuation; 7 is in both lists -> both bits; 9, 2 -> nothing
+    assert got.tolist() == [[1, 2, 3, 2, 0], [2, 1, 0, 3, 3]] and got.dtype == np.uint8
+    assert fo.classify_tokens(ids, [], []).tolist() == [[0] * 5, [0] * 5]
+    rng = np.random.default_rng(5)
+    big = rng.integers(0, 50, size=(3, 200))
+    sp, pu = [1, 2, 3], [3, 10, 20, 30]
+    ref = np.isin(big, sp).astype(np.uint8) | (np.isin(big, pu).astype(np.uint8) << 1)
+    assert np.array_equal(fo.classify_tokens(big, sp, pu), ref)
