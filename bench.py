@@ -228,7 +228,7 @@ def main():
 
     # ---- what library kernels reach on this machine, next to the published peaks (context only)
     ref = reference_rates(dev)
-    roof_profile["box_reference"] = {"bf16_gemm_8192_TFLOPs": ref["gemm_tflops"]}
+    roof_profile["box_reference"] = {"bf16_gemm_8192_TFLOPs": ref["gemm_tflops"], **pipe_microbenchmarks(dev)}
     if roof_decode:
         roof_decode["box_reference"] = {"device_copy_1GiB_GBps_read_plus_write": ref["copy_gbps"]}
     # the dominant kernel: the one the device spends most of a pass in
@@ -305,6 +305,39 @@ def reference_rates(dev):
     copy = 5 * 2 * float(1 << 30) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
     del src, dst
     return dict(gemm_tflops=gemm, copy_gbps=copy)
+
+
+def pipe_microbenchmarks(dev):
+    """Register-only micro-benchmarks of one wave-step of the sweeps (16 MFMAs of 32x32x16 bf16
+    and the softmax arithmetic of their 32 results per lane), three waves per SIMD: the matrix
+    pipe alone, the vector ALU alone, and both as the sweeps issue them. They give the rate the
+    matrix pipe sustains on this machine and show how far its work overlaps with the vector ALU's."""
+    import ctypes
+    import torch
+    path = os.path.join(ROOT, "paper_2310_01801_amd", "libfgubench.so")
+    if not os.path.exists(path):
+        return {"pipe_microbenchmarks": None}
+    lib = ctypes.CDLL(path)
+    lib.fg_ubench_run.restype = ctypes.c_int
+    lib.fg_ubench_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.POINTER(ctypes.c_double)]
+    blocks, iters = 768 * 4, 2000
+    out = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+    res = {}
+    for mode, name in ((1, "mfma_only"), (2, "softmax_valu_only_sweep1"), (3, "mfma_then_softmax_sweep1"),
+                       (4, "mfma_then_softmax_sweep2")):
+        ns = ctypes.c_double()
+        rc = lib.fg_ubench_run(mode, blocks, iters, out.data_ptr(), torch.cuda.current_stream().cuda_stream,
+                               ctypes.byref(ns))
+        if rc != 0:
+            return {"pipe_microbenchmarks": f"failed with HIP error {rc}"}
+        res[name + "_ns_per_wave_step"] = ns.value
+    flop = 16 * 2 * 32 * 32 * 16   # one wave-step of MFMAs
+    simds = 1024
+    res["mfma_only_TFLOPs"] = flop * simds / res["mfma_only_ns_per_wave_step"] / 1e3
+    res["sweep1_ceiling_frac_of_2.5PF"] = flop * simds / res["mfma_then_softmax_sweep1_ns_per_wave_step"] / 1e3 / 2500.0
+    res["sweep2_ceiling_frac_of_2.5PF"] = flop * simds / res["mfma_then_softmax_sweep2_ns_per_wave_step"] / 1e3 / 2500.0
+    return {"pipe_microbenchmarks": res}
 
 
 def cpu_baseline(w, plan, cls_p, cls_d, sample_units):

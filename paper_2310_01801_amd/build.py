@@ -10,6 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfastgen.so")
 SOURCES = ["fastgen_api.hip", "profile_mfma.hip", "profile_f32.hip", "select.hip", "decode.hip"]
+# measurement aid of bench.py (micro-benchmarks of the matrix and vector pipes), its own library
+UBENCH_LIB = os.path.join(HERE, "libfgubench.so")
+UBENCH_SOURCES = ["ubench.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -26,8 +29,8 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [hipcc(), *FLAGS, *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def _compile(sources, lib, verbose):
+    cmd = [hipcc(), *FLAGS, *[os.path.join(CSRC, s) for s in sources], "-o", lib]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -37,6 +40,11 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = True) -> str:
+    _compile(SOURCES, LIB, verbose)
+    _compile(UBENCH_SOURCES, UBENCH_LIB, verbose)
     return LIB
 
 

@@ -41,6 +41,21 @@ __device__ __forceinline__ void fg_unpack<4>(const u32x4& v, float* f) {
   for (int i = 0; i < 4; ++i) f[i] = __uint_as_float(v[i]);
 }
 
+// Dot product of the 8 bf16 pairs of two 16-byte chunks with float accumulation: four
+// two-element dot instructions instead of eight unpacks and eight multiply-adds. Serves the
+// output path only (the cumulative scores use the float64 logits).
+__device__ __forceinline__ float fg_dot_bf16x8(const u32x4& a, const u32x4& b) {
+  float acc = 0.f;
+  // (pairs taken from the 8-element vectors by shuffles: handed bit-cast dwords of the 128-bit
+  // vectors, the compiler of ROCm 7.2 selects element 0 for all four instructions)
+  const bf16x8 av = __builtin_bit_cast(bf16x8, a), bv = __builtin_bit_cast(bf16x8, b);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(av, av, 0, 1), __builtin_shufflevector(bv, bv, 0, 1), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(av, av, 2, 3), __builtin_shufflevector(bv, bv, 2, 3), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(av, av, 4, 5), __builtin_shufflevector(bv, bv, 4, 5), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(av, av, 6, 7), __builtin_shufflevector(bv, bv, 6, 7), acc, false);
+  return acc;
+}
+
 // GRP: several query heads per unit (a.G > 1); without it G is the constant 1 and the code is
 // the plain multi-head path.
 template <int ESIZE, int D, bool GRP>
@@ -92,10 +107,8 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
   const int G = GRP ? a.G : 1;
   const char* qu = static_cast<const char*>(a.q) + (size_t)u * G * RB;
   float qv[EPL];
-  {
-    const u32x4 t = *reinterpret_cast<const u32x4*>(qu + g * 16);
-    fg_unpack<ESIZE>(t, qv);
-  }
+  const u32x4 q_raw = *reinterpret_cast<const u32x4*>(qu + g * 16);   // this lane's 16 bytes of the query
+  fg_unpack<ESIZE>(q_raw, qv);
   // grouped heads: all G query vectors are staged in LDS while the cache rows are in flight
   __shared__ __attribute__((aligned(16))) unsigned char s_q[GRP ? 16 * RB : 16];
   if (GRP) {
@@ -244,8 +257,11 @@ __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a
       x[it] = ok ? (float)dd : FG_NEG_BIG;
     } else {
       float dot = 0.f;
+      if (ESIZE == 2) dot = fg_dot_bf16x8(q_raw, kv[it]);
+      else {
 #pragma unroll
-      for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+        for (int e = 0; e < EPL; ++e) dot = fmaf(qv[e], kf[e], dot);
+      }
       dot = fg_group_sum<LPR>(dot);
       x[it] = ok ? dot * c : FG_NEG_BIG;
     }

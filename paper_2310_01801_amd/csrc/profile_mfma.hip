@@ -36,7 +36,7 @@ struct Lds {
 };
 
 template <int D, int PASS>
-__global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
+__global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
     const __bf16* __restrict__ Q, const __bf16* __restrict__ K, float2* __restrict__ rowstat,
     double* __restrict__ colsum, double* __restrict__ bandcol, int U, int n, int w, float c,
     int nblk, int G) {
@@ -142,24 +142,29 @@ __global__ __launch_bounds__(256, 2) void fg_profile_mfma_kernel(
   double l_run[2] = {0.0, 0.0};
   double col_acc[2] = {0.0, 0.0}, band_acc[2] = {0.0, 0.0};          // pass 2
 
-  // Both sweeps walk their tiles upwards (walking the rows of sweep 2 downwards from the end,
-  // in lockstep or skewed by a few tiles per block so that the blocks of a unit share the
-  // streamed tiles in L2, measured the same time).
+  // Sweep 1 walks its tiles upwards. Sweep 2 walks the query rows downwards from the end of
+  // the prompt: every owner block of a unit then starts at the same tile and the blocks move
+  // in step, so a streamed tile is fetched into the XCD's L2 once per unit instead of once per
+  // block (walking upwards, block b reads a tile 8 steps after block b - 1 and six units per
+  // XCD outgrow the 4 MB L2: 3.5x the algorithmic bytes were fetched at n = 8192).
   const int nt = t_end - t_begin;     // tiles per head
   const int n_it = nt * heads;
   if (n_it > 0) {
-    gload(t_begin * kTile);
+    gload((PASS == 2 ? t_end - 1 : t_begin) * kTile);
     lstore(0);
   }
   __syncthreads();
 
-  int t = t_begin, head_row0 = 0;     // current tile and first row of the current head
+  int t = (PASS == 2) ? t_end - 1 : t_begin, head_row0 = 0;   // current tile and first row of the current head
   for (int it = 0; it < n_it; ++it) {
     const int buf = it & 1;
     const int t0 = t * kTile;
     // next tile: the following one of this head, else the first one of the next head
     int t_next = t + 1, head_next = head_row0;
-    if (t_next == t_end) { t_next = t_begin; head_next += n; }
+    if (PASS == 2) {
+      t_next = t - 1;
+      if (t_next < t_begin) { t_next = t_end - 1; head_next += n; }
+    } else if (t_next == t_end) { t_next = t_begin; head_next += n; }
     // unconditional (the load count per iteration is static); the last iteration re-reads its own tile
     gload(it + 1 < n_it ? head_next + t_next * kTile : head_row0 + t0);
 
