@@ -1,7 +1,9 @@
 // Prompt-time attention profiling for float32 inputs (Alg. 1: A = softmax(Q K^T); Sec. 3.4
 // cumulative attention score). Same two sweeps and the same outputs as the bf16 matrix-core
 // kernel, on the vector ALU: this is the path of the small float32 correctness workload,
-// not a throughput path. One thread owns one query row (pass 1) or one key column (pass 2)
+// not a throughput path, so it spends its time on accuracy instead: dot products, exponentials
+// and sums in float64 (products of two floats are exact there), only the stored row statistics
+// (m, 1/l) are floats. One thread owns one query row (pass 1) or one key column (pass 2)
 // with its vector in registers; the other matrix is streamed through LDS in tiles of 32.
 #include "fg_common.h"
 #include "fg_internal.h"
@@ -42,6 +44,7 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
 
   float m_run = FG_NEG_BIG;
   double l_run = 0.0, col_acc = 0.0, band_acc = 0.0;
+  const double c_d = (double)c;
 
   const int heads = (PASS == 1) ? 1 : G;
   for (int h = 0; h < heads; ++h) {
@@ -64,18 +67,18 @@ __global__ __launch_bounds__(256) void fg_profile_f32_kernel(
       if (s_idx >= n) break;
       if (PASS == 1 && s_idx > own) break;   // causal: column <= row
       if (PASS == 2 && s_idx < own) continue;  // causal: row >= column
-      float dot = 0.f;
+      double dot = 0.0;
 #pragma unroll
-      for (int k = 0; k < D; ++k) dot = fmaf(o[k], tile[it][k], dot);
-      const float x = dot * c;
+      for (int k = 0; k < D; ++k) dot = fma((double)o[k], (double)tile[it][k], dot);
+      const double x = dot * c_d;
       if (PASS == 1) {
-        const float m_new = fmaxf(m_run, x);
-        l_run = l_run * (double)fg_exp2(m_run - m_new) + (double)fg_exp2(x - m_new);
+        const float m_new = fmaxf(m_run, (float)x);   // a shift near the row's largest logit; any float will do
+        l_run = l_run * exp2((double)m_run - (double)m_new) + exp2(x - (double)m_new);
         m_run = m_new;
       } else {
-        const float p = fg_exp2(x - stat_t[it].x) * stat_t[it].y;
-        col_acc += (double)p;
-        if (s_idx - own < w) band_acc += (double)p;
+        const double p = exp2(x - (double)stat_t[it].x) * (double)stat_t[it].y;
+        col_acc += p;
+        if (s_idx - own < w) band_acc += p;
       }
     }
   }
