@@ -142,13 +142,13 @@ fg_status fastgen_profile(fastgen_ctx* ctx, const void* Q, const void* K,
 
 /* Stage 1a for callers that cannot allocate device memory and hold no workspace (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): fastgen_profile without
- * a context. The scratch its kernels need (row log-sum-exps, column and band sums, kept flags,
+ * a context. The scratch its kernels need (row statistics, column and band sums, kept flags,
  * per-unit results) lives in a static device array of 32 MiB inside the library, one copy per
  * GPU, held until the process ends; the call allocates nothing, on the host or the device.
  *   cfg          the configuration fastgen_create would take (max_new_tokens and cache_tokens
  *                only size the slot reservation and do not matter here). The shape is limited
- *                by the array: U * n * (4 * G + 21) + 112 * U bytes, each of the twelve regions
- *                rounded up to 256 bytes, must not exceed 32 MiB (e.g. U * n <= 1.3 M tokens at
+ *                by the array: U * n * (8 * G + 21) + 112 * U bytes, each of the twelve regions
+ *                rounded up to 256 bytes, must not exceed 32 MiB (e.g. U * n <= 1.1 M tokens at
  *                G = 1); larger shapes return FG_ENOMEM and launch nothing.
  *   Q, K, token_class, lse_opt, policy, recovery, kept_count, stream: as for fastgen_profile;
  *                the caller owns inputs and outputs. The device that owns `stream` must be the

@@ -1,8 +1,8 @@
 // One decode step over the ragged compressed caches (Alg. 2: attend with K^,V^ plus the new
 // token, then re-apply f with the head's policy; policies of Sec. 3.4).
 //
-//   fg_decode_partial_kernel  split-KV attention. The flat work list has one item per 256
-//       reserved slots of a unit (static after compaction); an item streams the K and V rows
+//   fg_decode_partial_kernel  split-KV attention. The flat work list has one item per 256 (128
+//       for short sequences) reserved slots of a unit (static after compaction); an item streams the K and V rows
 //       of its held slots with 16-byte-per-lane coalesced loads (a 256-byte bf16 row = 16
 //       lanes, 4 rows per wave load), keeps the scaled logits, and emits (max, sum, o) of its
 //       chunk. The item that owns the first free slot takes the new token from k_new/v_new
@@ -22,7 +22,6 @@
 
 namespace {
 
-constexpr int CH = FG_DECODE_CHUNK;
 constexpr int FG_MOVE_LDS = 64;  // released slots per step whose move lists stay in shared memory
 
 template <int ESIZE>
@@ -58,7 +57,7 @@ __device__ __forceinline__ float fg_dot_bf16x8(const u32x4& a, const u32x4& b) {
 
 // GRP: several query heads per unit (a.G > 1); without it G is the constant 1 and the code is
 // the plain multi-head path.
-template <int ESIZE, int D, bool GRP>
+template <int ESIZE, int D, bool GRP, int CH>
 __global__ __launch_bounds__(256) void fg_decode_partial_kernel(fg_decode_args a) {
   constexpr int RB = D * ESIZE;        // bytes per row
   constexpr int LPR = RB / 16;         // lanes per row
@@ -339,6 +338,7 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   const int64_t off = a.off[u];
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
+  const int CH = a.chunk;
   const int nch = (L + CH - 1) / CH;
   // the new length goes to len[] and into every work-item record of the unit
   auto set_len = [&](int v) {
@@ -655,20 +655,23 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   if (L <= 256 * 2) update(std::integral_constant<int, 2>{});
   else if (L <= 256 * 4) update(std::integral_constant<int, 4>{});
   else if (L <= 256 * 8) update(std::integral_constant<int, 8>{});
+  else if (L <= 256 * 12) update(std::integral_constant<int, 12>{});
+  else if (L <= 256 * 16) update(std::integral_constant<int, 16>{});
+  else if (L <= 256 * 20) update(std::integral_constant<int, 20>{});
   else update(std::integral_constant<int, 24>{});
 }
 
 }  // namespace
 
-template <bool GRP>
+template <bool GRP, int CH>
 static hipError_t launch_attn(const fg_decode_args& a, hipStream_t s) {
   const dim3 grid((unsigned)a.max_chunks), block(256);
   if (a.dtype == FG_BF16) {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<2, 128, GRP>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_partial_kernel<2, 64, GRP>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<2, 128, GRP, CH>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<2, 64, GRP, CH>), grid, block, 0, s, a);
   } else {
-    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<4, 128, GRP>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((fg_decode_partial_kernel<4, 64, GRP>), grid, block, 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((fg_decode_partial_kernel<4, 128, GRP, CH>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((fg_decode_partial_kernel<4, 64, GRP, CH>), grid, block, 0, s, a);
   }
   return hipGetLastError();
 }
@@ -687,7 +690,8 @@ static hipError_t launch_update(const fg_decode_args& a, hipStream_t s) {
 }
 
 hipError_t fg_launch_decode_attn(const fg_decode_args& a, hipStream_t s) {
-  return a.G > 1 ? launch_attn<true>(a, s) : launch_attn<false>(a, s);
+  if (a.chunk == 128) return a.G > 1 ? launch_attn<true, 128>(a, s) : launch_attn<false, 128>(a, s);
+  return a.G > 1 ? launch_attn<true, 256>(a, s) : launch_attn<false, 256>(a, s);
 }
 
 hipError_t fg_launch_decode_update(const fg_decode_args& a, hipStream_t s) {

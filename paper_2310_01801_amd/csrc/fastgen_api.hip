@@ -57,7 +57,7 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
     // the flat work list of the decode kernels (one item per 256 reserved slots) is a 32-bit grid
     const long long full = (long long)c->prompt_len + c->max_new_tokens;
     const long long pool = c->cache_tokens > 0 ? c->cache_tokens : (long long)c->num_units * full;
-    FG_REQUIRE(pool / FG_DECODE_CHUNK + c->num_units < (1ll << 31) - 1, "cache pool too large for the decode work list");
+    FG_REQUIRE(pool / fg_decode_chunk(c->prompt_len, c->max_new_tokens) + c->num_units < (1ll << 31) - 1, "cache pool too large for the decode work list");
   }
   FG_REQUIRE(c->group_size >= 0 && c->group_size <= 16, "group_size must be 0..16");
   bool any = false;
@@ -113,7 +113,8 @@ fg_layout make_layout(const fg_config& c) {
   const size_t full = n + (size_t)c.max_new_tokens;
   const size_t pool = c.cache_tokens > 0 ? (size_t)c.cache_tokens : U * full;
   L.pool_tokens = (int64_t)pool;
-  L.max_chunks = (int64_t)(pool / FG_DECODE_CHUNK + U);
+  L.chunk = fg_decode_chunk(c.prompt_len, c.max_new_tokens);
+  L.max_chunks = (int64_t)(pool / (size_t)L.chunk + U);
   size_t o = layout_profile_part(c, L);
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   L.ck = take(pool * d * e);
@@ -395,7 +396,7 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   hipError_t e = fg_launch_offsets(at<int32_t>(ctx, L.cap), at<int32_t>(ctx, L.len), at<int32_t>(ctx, L.policy),
                                    at<int64_t>(ctx, L.off), at<int32_t>(ctx, L.chunk_off), at<int32_t>(ctx, L.item_unit),
                                    at<int32_t>(ctx, L.flags), c.num_units, L.pool_tokens,
-                                   L.max_chunks, s);
+                                   L.max_chunks, L.chunk, s);
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(offsets)");
   fg_compact_args ca;
   ca.K = K; ca.V = V;
@@ -444,7 +445,7 @@ static fg_status decode_step_impl(fastgen_ctx* ctx, const void* q, const void* k
   da.U = c.num_units; da.n = c.prompt_len; da.d = c.head_dim; da.dtype = c.dtype;
   da.units_per_seq = c.num_units / c.num_seqs; da.w = ctx->w; da.step = ctx->steps_done;
   da.G = group_of(c);
-  da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks;
+  da.r_f = c.r_f; da.scale = ctx->scale; da.max_chunks = L.max_chunks; da.chunk = L.chunk;
   da.probe = probe;
   family_of(c, da.family);
   hipStream_t s = static_cast<hipStream_t>(stream);

@@ -42,6 +42,7 @@ struct fg_layout {
   size_t total;
   int64_t pool_tokens;
   int64_t max_chunks;
+  int chunk;        // tokens per decode work item (128 or 256)
 };
 
 struct fastgen_ctx {
@@ -63,7 +64,11 @@ struct fastgen_ctx {
   std::vector<hipEvent_t> spare;
 };
 
-constexpr int FG_DECODE_CHUNK = 256;  // tokens per split-KV work item
+// Tokens per split-KV work item of the decode kernels: 256 for long sequences, 128 when a unit
+// can hold at most 4096 tokens (finer items balance short caches better; measured per shape).
+inline int fg_decode_chunk(int prompt_len, int max_new_tokens) {
+  return ((long long)prompt_len + max_new_tokens <= 4096) ? 128 : 256;
+}
 
 // ---------------------------------------------------------------- launch arguments
 struct fg_profile_args {
@@ -105,6 +110,7 @@ struct fg_decode_args {
   double r_f;
   float scale;
   int64_t max_chunks;
+  int chunk;       // tokens per work item (128 or 256)
 };
 
 struct fg_export_args {
@@ -129,7 +135,7 @@ hipError_t fg_launch_select(const fg_select_args&, hipStream_t);
 hipError_t fg_launch_compact(const fg_compact_args&, hipStream_t);
 hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, const int32_t* policy, int64_t* off,
                              int32_t* chunk_off, int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens,
-                             int64_t max_chunks, hipStream_t);
+                             int64_t max_chunks, int chunk, hipStream_t);
 hipError_t fg_launch_decode_attn(const fg_decode_args&, hipStream_t);
 hipError_t fg_launch_decode_update(const fg_decode_args&, hipStream_t);
 hipError_t fg_launch_export(const fg_export_args&, hipStream_t);

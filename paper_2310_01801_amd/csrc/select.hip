@@ -136,12 +136,12 @@ __global__ __launch_bounds__(256) void fg_select_kernel(fg_select_args a) {
   }
 }
 
-// Single workgroup: off[u] = sum_{v<u} cap[v]; chunk_off[u] = sum_{v<u} ceil(cap[v]/CHUNK).
+// Single workgroup: off[u] = sum_{v<u} cap[v]; chunk_off[u] = sum_{v<u} ceil(cap[v]/chunk).
 __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restrict__ cap,
                                                           int64_t* __restrict__ off,
                                                           int32_t* __restrict__ chunk_off,
                                                           int32_t* __restrict__ flags, int U,
-                                                          int64_t pool_tokens, int64_t max_chunks) {
+                                                          int64_t pool_tokens, int64_t max_chunks, int chunk) {
   __shared__ int red[20];
   __shared__ long long wsum[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restr
   for (int base = 0; base < U; base += 1024) {
     const int u = base + tid;
     const int c = (u < U) ? cap[u] : 0;
-    const int nch = (c + FG_DECODE_CHUNK - 1) / FG_DECODE_CHUNK;
+    const int nch = (c + chunk - 1) / chunk;
     int total;
     const int exc = fg_block_exscan_i32(nch, red, &total);
     // 64-bit scan of the capacities: wave scan + serial over the 16 waves
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(1024) void fg_offsets_kernel(const int32_t* __restr
 }
 
 // Work-item records of the decode attention kernel: item c of unit u covers slots
-// [256 * (c - chunk_off[u]), +256) of that unit. 8 ints per item: unit, chunk, cap, tokens held
+// [chunk * (c - chunk_off[u]), +chunk) of that unit (chunk = 128 or 256 tokens). 8 ints per item: unit, chunk, cap, tokens held
 // by the unit (kept current by the update kernel), off lo, off hi, policy word (id | component
 // mask << 8), 0.
 __global__ __launch_bounds__(256) void fg_item_map_kernel(const int32_t* __restrict__ chunk_off,
@@ -338,9 +338,9 @@ hipError_t fg_launch_compact(const fg_compact_args& a, hipStream_t s) {
 
 hipError_t fg_launch_offsets(const int32_t* cap, const int32_t* len, const int32_t* policy, int64_t* off,
                              int32_t* chunk_off, int32_t* item_unit, int32_t* flags, int U, int64_t pool_tokens,
-                             int64_t max_chunks, hipStream_t s) {
+                             int64_t max_chunks, int chunk, hipStream_t s) {
   hipLaunchKernelGGL(fg_offsets_kernel, dim3(1), dim3(1024), 0, s, cap, off, chunk_off, flags, U,
-                     pool_tokens, max_chunks);
+                     pool_tokens, max_chunks, chunk);
   hipLaunchKernelGGL(fg_item_map_kernel, dim3((unsigned)((U + 255) / 256)), dim3(256), 0, s,
                      chunk_off, cap, off, len, policy, item_unit, flags, U);
   return hipGetLastError();

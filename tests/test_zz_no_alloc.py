@@ -53,7 +53,7 @@ def test_static_scratch_profile_twice_second_call_smaller():
 
 def test_static_scratch_rejects_what_does_not_fit():
     lib = binding.load_library()
-    # 1024 units x 2048 tokens need ~54 MB of scratch: more than the 32 MiB array
+    # 1024 units x 2048 tokens need ~61 MB of scratch: more than the 32 MiB array
     cfg = binding.make_config(1024, 1, 128, torch.bfloat16, 2048, 0, 0.95, 0.3, 0.3)
     x = torch.zeros(64, dtype=torch.uint8, device="cuda:0")
     st = lib.fastgen_profile_static(ctypes.byref(cfg), x.data_ptr(), x.data_ptr(), x.data_ptr(), None, None, None,
