@@ -67,14 +67,14 @@ def decode_bytes(lens_before, policy, d, e):
     """Algorithmic HBM bytes of one decode step: (attention kernel, whole step).
     Per unit with L = held tokens including the new one: K^ and V^ rows 2*L*d*e; q, k_new,
     v_new read and o written 4*d*e; the appended row 2*d*e; for the policies that keep
-    cumulative scores (those with `frequent`) the logit of every held token written once
-    (4*L). The update adds: positions and classes (5*L) for the policies that evict, logits
-    read (4*L) and cumulative scores read+written (16*L) for those with `frequent`."""
+    cumulative scores (those with `frequent`) the float64 logit of every held token written
+    once (8*L). The update adds: positions and classes (5*L) for the policies that evict, logits
+    read (8*L) and cumulative scores read+written (16*L) for those with `frequent`."""
     import numpy as np
     L = lens_before.astype(np.int64) + 1
     scored = (policy == 2) | (policy == 3)
-    attn = 2 * L * d * e + 5 * d * e + np.where(scored, 4 * L, 0)
-    upd = d * e + np.where(policy < 4, 5 * L, 0) + np.where(scored, 20 * L, 0)
+    attn = 2 * L * d * e + 5 * d * e + np.where(scored, 8 * L, 0)
+    upd = d * e + np.where(policy < 4, 5 * L, 0) + np.where(scored, 24 * L, 0)
     return int(attn.sum()), int(attn.sum() + upd.sum())
 
 
