@@ -54,7 +54,7 @@ bool config_ok(const fg_config* c, char* why, size_t why_len) {
   FG_REQUIRE(c->forced_policy >= -1 && c->forced_policy <= 4, "forced_policy must be -1..4");
   FG_REQUIRE(c->cache_tokens >= 0, "cache_tokens must be >= 0");
   {
-    // the flat work list of the decode kernels (one item per 256 reserved slots) is a 32-bit grid
+    // the flat work list of the decode kernels (one item per 128 or 256 reserved slots) is a 32-bit grid
     const long long full = (long long)c->prompt_len + c->max_new_tokens;
     const long long pool = c->cache_tokens > 0 ? c->cache_tokens : (long long)c->num_units * full;
     FG_REQUIRE(pool / fg_decode_chunk(c->prompt_len, c->max_new_tokens) + c->num_units < (1ll << 31) - 1, "cache pool too large for the decode work list");
@@ -400,7 +400,6 @@ fg_status fastgen_compact(fastgen_ctx* ctx, const void* K, const void* V, void* 
   if (e != hipSuccess) return hip_fail(ctx, e, "fastgen_compact(offsets)");
   fg_compact_args ca;
   ca.K = K; ca.V = V;
-  ca.token_class = nullptr;  // class bits travel inside the keep bytes
   ca.colsum = at<double>(ctx, L.colsum); ca.keep = at<uint8_t>(ctx, L.keep);
   ca.slot = at<int32_t>(ctx, L.slot); ca.cap = at<int32_t>(ctx, L.cap);
   ca.off = at<int64_t>(ctx, L.off); ca.len = at<int32_t>(ctx, L.len);

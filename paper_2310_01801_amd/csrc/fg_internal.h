@@ -92,7 +92,7 @@ struct fg_select_args {
 
 struct fg_compact_args {
   const void* K; const void* V;
-  const uint8_t* token_class; const double* colsum; const uint8_t* keep; const int32_t* slot;
+  const double* colsum; const uint8_t* keep; const int32_t* slot;   // keep: 0, or 4 | class bits
   const int32_t* cap; int64_t* off; const int32_t* len; int32_t* flags;
   void* ck; void* cv; double* cscore; int32_t* cpos; uint8_t* ccls;
   int U, n, d, esize, units_per_seq;

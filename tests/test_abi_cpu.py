@@ -113,3 +113,17 @@ def test_classify_rejects_bad_arguments_on_the_host(lib):
     assert call(fake, 8, ids, 65, None, 0, fake, None) == binding.FG_EINVAL        # more than 64 ids
     assert b"at most 64" in lib.fastgen_last_error(None)
     assert call(fake, 8, None, 3, None, 0, fake, None) == binding.FG_EINVAL        # a count without a list
+
+
+def test_microbenchmark_library_loads_and_rejects_bad_arguments(lib):
+    # the measurement aid of bench.py: built next to the main library, one C entry point
+    path = os.path.join(os.path.dirname(binding.LIB_PATH), "libfgubench.so")
+    assert os.path.exists(path), "python -m paper_2310_01801_amd.build builds it"
+    ub = ctypes.CDLL(path)
+    ub.fg_ubench_run.restype = ctypes.c_int
+    ub.fg_ubench_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                 ctypes.POINTER(ctypes.c_double)]
+    ns = ctypes.c_double()
+    assert ub.fg_ubench_run(0, 1, 1, 0x10000, None, ctypes.byref(ns)) == -1      # mode out of range
+    assert ub.fg_ubench_run(1, 0, 1, 0x10000, None, ctypes.byref(ns)) == -1
+    assert ub.fg_ubench_run(1, 1, 1, None, None, ctypes.byref(ns)) == -1
