@@ -60,6 +60,8 @@ def parse():
                     help="query heads per K/V head (grouped-query variant of the workload; not a BASELINE config)")
     ap.add_argument("--forced-policy", type=int, default=-1, help="every unit uses this policy (non-adaptive baselines)")
     ap.add_argument("--cpu-sample-units", type=int, default=0, help="0 = sized for ~20 s")
+    ap.add_argument("--probe-every", type=int, default=0,
+                    help="N > 0: every N-th decode step runs with the stability probe (fastgen_decode_step_probe)")
     return ap.parse_args()
 
 
@@ -119,7 +121,10 @@ def run_workload(w, args, steps, warmup, dev="cuda:0"):
         fg.fastgen_compact(K, V)
         ev[1].record()
         for t in range(S):
-            fg.fastgen_decode_step(q[t], k[t], v[t], cls_d_d[t], out)
+            if args.probe_every > 0 and t % args.probe_every == 0:
+                fg.fastgen_decode_step_probe(q[t], k[t], v[t], cls_d_d[t], out)
+            else:
+                fg.fastgen_decode_step(q[t], k[t], v[t], cls_d_d[t], out)
         ev[2].record()
         torch.cuda.synchronize()
         res = dict(stage1_ms=ev[0].elapsed_time(ev[1]), stage2_ms=ev[1].elapsed_time(ev[2]),
@@ -241,7 +246,8 @@ def main():
 
     # ---- the other bf16 configurations, short side runs (1 warm-up + 3 timed passes each)
     others = None
-    if not args.no_other_configs and args.forced_policy < 0 and args.group_size <= 1 and args.decode_steps < 0:
+    if (not args.no_other_configs and args.forced_policy < 0 and args.group_size <= 1 and args.decode_steps < 0
+            and args.probe_every == 0):
         others = {}
         for name in ("llama7b_b1", "llama7b_b16", "llama13b_b4", "llama65b_b2"):
             if name == w.name:
