@@ -500,6 +500,6 @@ fg_status fastgen_export_state(fastgen_ctx* ctx, int32_t* lengths, int64_t* offs
 
 const char* fastgen_last_error(const fastgen_ctx* ctx) { return ctx ? ctx->err : g_static_err; }
 
-const char* fastgen_version(void) { return "fastgen-mi355x 0.1 (gfx950)"; }
+const char* fastgen_version(void) { return "fastgen-mi355x 0.2 (gfx950)"; }
 
 }  // extern "C"
