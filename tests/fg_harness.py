@@ -30,7 +30,9 @@ MARGIN_EPS = 1e-4
 # on the bf16 matrix cores with float32 accumulation (resolution ~1e-7 of a logit of size 10,
 # i.e. ~1e-7 relative in an attention weight), so two cumulative scores closer than a few 1e-7
 # cannot be ordered reliably; the largest score error the suite observes among tokens within
-# 1 % of a boundary is 4e-7 (reported per test as "near the top-k boundary"). The band is 5x that.
+# 1 % of a boundary is 3-5e-7 at the benchmark prompt lengths and up to 1e-6 for prompts of ~100
+# tokens (reported per test as "near the top-k boundary"). The band is 2-5x that. In every run so
+# far no comparison made under this tolerance has actually differed (the report counts them).
 GAP_EPS = 2e-6
 GAP_ABS = 1e-30         # scores this small are below float32's exponent range on the GPU
 TIE_BAND = 2e-5         # tokens swapped at a near-tie lie this close (relative) to the boundary score
