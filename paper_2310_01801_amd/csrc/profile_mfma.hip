@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
   static_assert(LOADS >= 1, "tile too small");
 
   __shared__ __attribute__((aligned(16))) unsigned char tile_lds[2][Lds<D>::kTileBytes];
-  __shared__ __attribute__((aligned(16))) float stat_lds[2][2][kTile];  // [buffer][m | 1/l][row]
+  __shared__ __attribute__((aligned(16))) float stat_lds[2][kTile * 2];  // [buffer][row][m, 1/l]
 
   // ---- which (unit, owner block): units of one XCD walk one unit's blocks back to back
   const int idx = blockIdx.x;
@@ -102,9 +102,15 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
     t_end = (n + kTile - 1) / kTile;
   }
 
-  // Streamed tiles come through raw buffer loads: the per-thread byte offset is fixed, the
-  // tile offset is a scalar, and rows past the end of the unit read as zeros (every use of
-  // them is masked), so a load costs no vector-ALU instruction.
+  // Streamed tiles come through raw buffer loads: the tile offset is a scalar and rows past the
+  // end of the unit read as zeros (every use of them is masked), so a load costs no vector-ALU
+  // instruction. In the first sweep at head dimension 128 the loads write straight into LDS (no
+  // staging registers, no LDS store instructions): a wave brings eight of the tile's 32 rows,
+  // one 256-byte row per instruction (a dword per lane), so that every row lands at its padded
+  // position. (Measured: about 3.5 % off the first sweep; the second sweep, which also streams
+  // the row statistics, did not gain from it and keeps the register staging.)
+  constexpr bool DMA = (D == 128) && (PASS == 1);
+  typedef __attribute__((address_space(3))) void* lds_ptr;
   const __amdgpu_buffer_rsrc_t str_rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(str_mat), 0, heads * n * D * 2, 0x00020000);
   const __amdgpu_buffer_rsrc_t stat_rsrc =
@@ -120,21 +126,31 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
   float2 stage_stat = make_float2(0.f, 0.f);
   // `row0` = first streamed row of the tile counted over all heads (head * n + t * 32); a tile
   // that runs past its head's last row reads the next head's rows (or zeros after the last
-  // head): those rows are masked wherever they are used.
-  auto gload = [&](int row0) {
+  // head): those rows are masked wherever they are used. `buf` is the LDS buffer the tile is for.
+  auto gload = [&](int row0, int buf) {
+    if (DMA) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int row = wave * 8 + r;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(str_rsrc, (lds_ptr)&tile_lds[buf][row * RS], 4, lane * 4,
+                                                 (row0 + row) * (D * 2), 0, 0);
+      }
+      return;
+    }
 #pragma unroll
     for (int r = 0; r < LOADS; ++r)
       stage[r] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(str_rsrc, voff[r], row0 * (D * 2), 0));
     if (PASS == 2) stage_stat = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(stat_rsrc, voff_stat, row0 * 8, 0));
   };
   auto lstore = [&](int buf) {
+    if (DMA) return;   // the loads have written LDS themselves; the barrier that follows waits for them
 #pragma unroll
     for (int r = 0; r < LOADS; ++r) {
       const int q = tid + 256 * r;
       const int item = q / CHUNKS_PER_ROW, ch = q % CHUNKS_PER_ROW;
       *reinterpret_cast<u32x4*>(&tile_lds[buf][item * RS + ch * 16]) = stage[r];
     }
-    if (PASS == 2 && tid < kTile) { stat_lds[buf][0][tid] = stage_stat.x; stat_lds[buf][1][tid] = stage_stat.y; }
+    if (PASS == 2 && tid < kTile) *reinterpret_cast<float2*>(&stat_lds[buf][tid * 2]) = stage_stat;
   };
 
   // ---- per-lane running statistics
@@ -150,7 +166,7 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
   const int nt = t_end - t_begin;     // tiles per head
   const int n_it = nt * heads;
   if (n_it > 0) {
-    gload((PASS == 2 ? t_end - 1 : t_begin) * kTile);
+    gload((PASS == 2 ? t_end - 1 : t_begin) * kTile, 0);
     lstore(0);
   }
   __syncthreads();
@@ -166,7 +182,7 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
       if (t_next < t_begin) { t_next = t_end - 1; head_next += n; }
     } else if (t_next == t_end) { t_next = t_begin; head_next += n; }
     // unconditional (the load count per iteration is static); the last iteration re-reads its own tile
-    gload(it + 1 < n_it ? head_next + t_next * kTile : head_row0 + t0);
+    gload(it + 1 < n_it ? head_next + t_next * kTile : head_row0 + t0, buf ^ 1);
 
     // what this wave has to do with the tile, per owner fragment
     bool need[2];
@@ -237,10 +253,10 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
         float ms[16], il[16];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const f32x4 v = *reinterpret_cast<const f32x4*>(&stat_lds[buf][0][g * 8 + lh * 4]);
-          const f32x4 u = *reinterpret_cast<const f32x4*>(&stat_lds[buf][1][g * 8 + lh * 4]);
-          ms[g * 4 + 0] = v[0]; ms[g * 4 + 1] = v[1]; ms[g * 4 + 2] = v[2]; ms[g * 4 + 3] = v[3];
-          il[g * 4 + 0] = u[0]; il[g * 4 + 1] = u[1]; il[g * 4 + 2] = u[2]; il[g * 4 + 3] = u[3];
+          const f32x4 v = *reinterpret_cast<const f32x4*>(&stat_lds[buf][(g * 8 + lh * 4) * 2]);      // m0 i0 m1 i1
+          const f32x4 u = *reinterpret_cast<const f32x4*>(&stat_lds[buf][(g * 8 + lh * 4) * 2 + 4]);  // m2 i2 m3 i3
+          ms[g * 4 + 0] = v[0]; ms[g * 4 + 1] = v[2]; ms[g * 4 + 2] = u[0]; ms[g * 4 + 3] = u[2];
+          il[g * 4 + 0] = v[1]; il[g * 4 + 1] = v[3]; il[g * 4 + 2] = u[1]; il[g * 4 + 3] = u[3];
         }
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
@@ -256,6 +272,33 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
             for (int i = 0; i < 16; ++i) s = fmaf(fg_exp2(fmaf(acc[f][i], c, -ms[i])), il[i], s);
             col_acc[f] += (double)s;
             if (inside) band_acc[f] += (double)s;  // the whole tile lies in the local band
+          } else if (full) {
+            // the band's edge crosses the tile (nothing else to mask): the total needs no
+            // mask, the band sum takes the terms with row - col < w
+            const int blim = w - (sbase - col);   // row - col < w  iff  (i>>2)*8 + (i&3) < blim
+            float s = 0.f, sb = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const float e = fg_exp2(fmaf(acc[f][i], c, -ms[i]));
+              s = fmaf(e, il[i], s);
+              sb = fmaf(e, ((i >> 2) * 8 + (i & 3)) < blim ? il[i] : 0.f, sb);
+            }
+            col_acc[f] += (double)s;
+            band_acc[f] += (double)sb;
+          } else if (inside) {
+            // diagonal and / or last tile, wholly within the band: one mask, band sum = total
+            const int dbase = sbase - col;
+            const int rlim = n - sbase;
+            float s = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int o = (i >> 2) * 8 + (i & 3);
+              const bool ok = (dbase + o >= 0) && (o < rlim);
+              const float e = fg_exp2(fmaf(acc[f][i], c, -ms[i]));   // may be huge where masked: select, do not scale
+              s = fmaf(ok ? e : 0.f, il[i], s);
+            }
+            col_acc[f] += (double)s;
+            band_acc[f] += (double)s;
           } else {
             const int dbase = sbase - col;        // row - col = dbase + (i>>2)*8 + (i&3)
             const int rlim = n - sbase;           // row < n  iff  (i>>2)*8 + (i&3) < rlim
