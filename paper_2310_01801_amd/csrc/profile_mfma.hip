@@ -223,9 +223,9 @@ __global__ __launch_bounds__(256, 3) void fg_profile_mfma_kernel(
             const float x4 = fmaxf(fmaxf(ac[12], ac[13]), ac[14]);
             const float y0 = fmaxf(fmaxf(x0, x1), x2), y1 = fmaxf(fmaxf(x3, x4), ac[15]);
             const float m_new = fmaxf(fmaxf(y0, y1) * c, m_run[f]);
-            float s = 0.f;
+            float s = fg_exp2(fmaf(acc[f][0], c, -m_new));
 #pragma unroll
-            for (int i = 0; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
+            for (int i = 1; i < 16; ++i) s += fg_exp2(fmaf(acc[f][i], c, -m_new));
             l_run[f] = l_run[f] * (double)fg_exp2(m_run[f] - m_new) + (double)s;
             m_run[f] = m_new;
           } else {  // diagonal tile: causal mask col <= row
