@@ -330,18 +330,21 @@ def pipe_microbenchmarks(dev):
     lib = ctypes.CDLL(path)
     lib.fg_ubench_run.restype = ctypes.c_int
     lib.fg_ubench_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
-                                  ctypes.POINTER(ctypes.c_double)]
+                                  ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     blocks, iters = 768 * 4, 2000
     out = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+    clk = torch.zeros(2 * blocks, dtype=torch.int64, device=dev)
     res = {}
     for mode, name in ((1, "mfma_only"), (2, "softmax_valu_only_sweep1"), (3, "mfma_then_softmax_sweep1"),
                        (4, "mfma_then_softmax_sweep2")):
-        ns = ctypes.c_double()
-        rc = lib.fg_ubench_run(mode, blocks, iters, out.data_ptr(), torch.cuda.current_stream().cuda_stream,
-                               ctypes.byref(ns))
+        ns, mhz = ctypes.c_double(), ctypes.c_double()
+        rc = lib.fg_ubench_run(mode, blocks, iters, out.data_ptr(), clk.data_ptr(),
+                               torch.cuda.current_stream().cuda_stream, ctypes.byref(ns), ctypes.byref(mhz))
         if rc != 0:
             return {"pipe_microbenchmarks": f"failed with HIP error {rc}"}
         res[name + "_ns_per_wave_step"] = ns.value
+        # the shader clock the chip held meanwhile (cycle counter / 100 MHz counter)
+        res[name + "_shader_MHz"] = mhz.value
     flop = 16 * 2 * 32 * 32 * 16   # one wave-step of MFMAs
     simds = 1024
     res["mfma_only_TFLOPs"] = flop * simds / res["mfma_only_ns_per_wave_step"] / 1e3

@@ -16,13 +16,19 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "fg_common.h"
 
 namespace {
 
 template <int MODE>
-__global__ __launch_bounds__(256, 3) void fg_ubench_kernel(float* __restrict__ out, int iters, float c) {
+__global__ __launch_bounds__(256, 3) void fg_ubench_kernel(float* __restrict__ out, unsigned long long* __restrict__ clk,
+                                                           int iters, float c) {
   const int tid = threadIdx.x;
+  // shader-clock and constant-rate (100 MHz) counters around the loop: their ratio is the clock
+  // the chip actually holds under this instruction mix
+  const unsigned long long c0 = clock64(), w0 = wall_clock64();
   bf16x8 a[8], b0[8], b1[8];
 #pragma unroll
   for (int kk = 0; kk < 8; ++kk) {
@@ -88,11 +94,15 @@ __global__ __launch_bounds__(256, 3) void fg_ubench_kernel(float* __restrict__ o
     }
   }
   out[(size_t)blockIdx.x * 256 + tid] = (float)(l_run[0] + l_run[1]) + m_run[0] + m_run[1];
+  if (clk != nullptr && tid == 0) {
+    clk[2 * blockIdx.x] = clock64() - c0;
+    clk[2 * blockIdx.x + 1] = wall_clock64() - w0;
+  }
 }
 
 template <int MODE>
-hipError_t run(float* out, int blocks, int iters, hipStream_t s) {
-  hipLaunchKernelGGL((fg_ubench_kernel<MODE>), dim3((unsigned)blocks), dim3(256), 0, s, out, iters, 0.1275f);
+hipError_t run(float* out, unsigned long long* clk, int blocks, int iters, hipStream_t s) {
+  hipLaunchKernelGGL((fg_ubench_kernel<MODE>), dim3((unsigned)blocks), dim3(256), 0, s, out, clk, iters, 0.1275f);
   return hipGetLastError();
 }
 
@@ -103,11 +113,17 @@ extern "C" {
 // Runs one micro-benchmark: `blocks` workgroups of four waves, `iters` wave-steps per wave.
 //   mode        1..4, see the head of this file
 //   out         device float[blocks * 256], written (results are meaningless, they keep the work alive)
+//   clk         device uint64[2 * blocks] or NULL: per workgroup, shader-clock cycles and 100 MHz ticks
+//               spent in the loop (written by the timed launch)
 //   ns_per_wave_step  host: measured time / iters x (waves per SIMD in flight), i.e. the time one SIMD
 //               needs per wave-step when `blocks` fills the chip evenly (a multiple of 768 on 256 CUs)
+//   shader_mhz  host or NULL (needs clk): the shader clock held during the timed launch, averaged
+//               over the workgroups (cycles / ticks x 100 MHz)
 // Returns 0, or a HIP error code. Synchronises the stream.
-int fg_ubench_run(int mode, int blocks, int iters, float* out, void* stream, double* ns_per_wave_step) {
+int fg_ubench_run(int mode, int blocks, int iters, float* out, unsigned long long* clk, void* stream,
+                  double* ns_per_wave_step, double* shader_mhz) {
   if (mode < 1 || mode > 4 || blocks < 1 || iters < 1 || !out || !ns_per_wave_step) return -1;
+  if (shader_mhz && !clk) return -1;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipEvent_t e0, e1;
   hipError_t e = hipEventCreate(&e0);
@@ -116,10 +132,10 @@ int fg_ubench_run(int mode, int blocks, int iters, float* out, void* stream, dou
   if (e != hipSuccess) { (void)hipEventDestroy(e0); return (int)e; }
   auto launch = [&]() {
     switch (mode) {
-      case 1: return run<1>(out, blocks, iters, s);
-      case 2: return run<2>(out, blocks, iters, s);
-      case 3: return run<3>(out, blocks, iters, s);
-      default: return run<4>(out, blocks, iters, s);
+      case 1: return run<1>(out, clk, blocks, iters, s);
+      case 2: return run<2>(out, clk, blocks, iters, s);
+      case 3: return run<3>(out, clk, blocks, iters, s);
+      default: return run<4>(out, clk, blocks, iters, s);
     }
   };
   e = launch();  // warm-up
@@ -135,6 +151,14 @@ int fg_ubench_run(int mode, int blocks, int iters, float* out, void* stream, dou
   // wave-steps per SIMD = iters * (waves per SIMD) = iters * blocks / 256 CUs (one wave of a block per SIMD)
   const double per_simd = (double)iters * (double)blocks / 256.0;
   *ns_per_wave_step = (double)ms * 1e6 / per_simd;
+  if (shader_mhz) {
+    std::vector<unsigned long long> h(2 * (size_t)blocks);
+    e = hipMemcpy(h.data(), clk, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return (int)e;
+    double cyc = 0.0, ticks = 0.0;
+    for (int b = 0; b < blocks; ++b) { cyc += (double)h[2 * b]; ticks += (double)h[2 * b + 1]; }
+    *shader_mhz = ticks > 0.0 ? cyc / ticks * 100.0 : 0.0;
+  }
   return 0;
 }
 

@@ -122,8 +122,9 @@ def test_microbenchmark_library_loads_and_rejects_bad_arguments(lib):
     ub = ctypes.CDLL(path)
     ub.fg_ubench_run.restype = ctypes.c_int
     ub.fg_ubench_run.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
-                                 ctypes.POINTER(ctypes.c_double)]
-    ns = ctypes.c_double()
-    assert ub.fg_ubench_run(0, 1, 1, 0x10000, None, ctypes.byref(ns)) == -1      # mode out of range
-    assert ub.fg_ubench_run(1, 0, 1, 0x10000, None, ctypes.byref(ns)) == -1
-    assert ub.fg_ubench_run(1, 1, 1, None, None, ctypes.byref(ns)) == -1
+                                 ctypes.c_void_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    ns, mhz = ctypes.c_double(), ctypes.c_double()
+    assert ub.fg_ubench_run(0, 1, 1, 0x10000, None, None, ctypes.byref(ns), None) == -1      # mode out of range
+    assert ub.fg_ubench_run(1, 0, 1, 0x10000, None, None, ctypes.byref(ns), None) == -1
+    assert ub.fg_ubench_run(1, 1, 1, None, None, None, ctypes.byref(ns), None) == -1
+    assert ub.fg_ubench_run(1, 1, 1, 0x10000, None, None, ctypes.byref(ns), ctypes.byref(mhz)) == -1  # clock without its buffer
