@@ -57,6 +57,20 @@ def test_small_shapes(n, S, d, dtype):
     _report(f"n={n} S={S} d={d} {dtype}", rep)
 
 
+@pytest.mark.parametrize("w_tokens", [1, 4, 31, 32, 33, 63, 64, 65, 97, 200, 399, 400])
+def test_local_window_widths_across_tile_edges(w_tokens):
+    # the second sweep treats a 32-row tile by where the local band's edge falls in it (outside,
+    # inside, crossing, on the diagonal): window widths around the tile size and its multiples,
+    # on a prompt with a ragged last tile; d = 128 and d = 64 take different staging paths
+    n = 400
+    for d in (128, 64):
+        w = W["llama7b_b1"].scaled(name=f"band_{w_tokens}_{d}", layers=1, heads=6, batch=1, prompt_len=n, steps=3,
+                                   head_dim=d, r_l=min(1.0, (w_tokens + 0.5) / n), seed=500 + w_tokens)
+        run = H.GpuRun(w, range(w.num_units))
+        rep = H.compare(run)
+        _report(f"local window of {w_tokens} tokens, n={n}, d={d}", rep)
+
+
 @pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
 def test_forced_policies(policy):
     w = W["llama7b_b1"].scaled(name="forced", layers=1, heads=10, batch=1, prompt_len=300, steps=40, seed=7)
