@@ -33,10 +33,10 @@ TIMING_SAMPLE = 8         # decode steps between two timed ones (an event record
 # decode steps.
 MEASURED_TRAFFIC = {
     # (FETCH_SIZE KiB x 2 + WRITE_SIZE KiB) x 1024 of sweep 1 + sweep 2; of fg_decode_partial_kernel
-    "llama65b_b2": {"sweeps": (29027586 * 2 + 655360 + 35091520 * 2 + 2293060) * 1024.0,
-                    "decode_attn": (9838031 * 2 + 274782) * 1024.0},
-    "llama7b_b1": {"sweeps": (673081 * 2 + 16384 + 736380 * 2 + 57342) * 1024.0,
-                   "decode_attn": (263545 * 2 + 8097) * 1024.0},
+    "llama65b_b2": {"sweeps": (26371393 * 2 + 655360 + 32501777 * 2 + 2129920) * 1024.0,
+                    "decode_attn": (9837948 * 2 + 274801) * 1024.0},
+    "llama7b_b1": {"sweeps": (717242 * 2 + 16384 + 736650 * 2 + 53248) * 1024.0,
+                   "decode_attn": (263969 * 2 + 10228) * 1024.0},
 }
 
 BASELINE_INDEX = {"tiny": 0, "llama7b_b1": 1, "llama7b_b16": 2, "llama13b_b4": 3, "llama65b_b2": 4}
