@@ -326,24 +326,35 @@ __global__ __launch_bounds__(256, GRP ? 2 : 4) void fg_decode_finish_kernel(fg_d
   __shared__ float s_M[16];  // per query head: merged maximum of the scaled logits
   const int u = blockIdx.x, tid = threadIdx.x;
   const int G = GRP ? a.G : 1;
-  // independent header loads first, then the checks
-  const int overflow = a.flags[0];
-  const int Lold = a.len[u], cap = a.cap[u], c_off = a.chunk_off[u], pword = a.policy[u];
+  // Every header word is fetched before the first check, through the constant address space
+  // (scalar loads, all in flight together; the empty asm statements pin the order): nothing
+  // here writes what they read before the kernel's last step (len[u]), or only 0 -> 1 (the flag).
+  typedef const __attribute__((address_space(4))) int32_t* cptr;
+  typedef const __attribute__((address_space(4))) int64_t* cptr8;
+  const int32_t *flags_p = a.flags, *len_p = a.len + u, *cap_p = a.cap + u, *coff_p = a.chunk_off + u,
+                *pol_p = a.policy + u;
+  const int64_t* off_p = a.off + u;
+  asm volatile("" ::"s"(flags_p), "s"(len_p), "s"(cap_p), "s"(coff_p), "s"(pol_p), "s"(off_p), "s"(a.part), "s"(a.out));
+  const int overflow = *(cptr)(uintptr_t)flags_p;
+  const int Lold = *(cptr)(uintptr_t)len_p, cap = *(cptr)(uintptr_t)cap_p, c_off = *(cptr)(uintptr_t)coff_p,
+            pword = *(cptr)(uintptr_t)pol_p;
+  const int64_t off = *(cptr8)(uintptr_t)off_p;
+  asm volatile("" ::"s"(overflow), "s"(Lold), "s"(cap), "s"(c_off), "s"(pword), "s"(off));
   // policy word: id in the low byte, the policy's component mask (FG_COMP_*) above it
   const int policy = pword & 0xff, comp = pword >> 8;
   const bool freq = (comp & FG_COMP_FREQUENT) != 0;
   // the stability probe needs the cumulative scores and their top-k for every policy
   const bool probing = a.probe != nullptr;
   const bool scored = freq || probing;
-  const int64_t off = a.off[u];
   const int L = Lold + 1;
   if (overflow != 0 || L > cap) return;
-  const int CH = a.chunk;
-  const int nch = (L + CH - 1) / CH;
+  const int CH = a.chunk;                      // a power of two
+  const int ch_shift = 31 - __builtin_clz(CH);
+  const int nch = (L + CH - 1) >> ch_shift;
   // the new length goes to len[] and into every work-item record of the unit
   auto set_len = [&](int v) {
     if (tid == 0) a.len[u] = v;
-    for (int i = tid; i < (cap + CH - 1) / CH; i += 256) a.item_unit[(size_t)(c_off + i) * 8 + 3] = v;
+    for (int i = tid; i < ((cap + CH - 1) >> ch_shift); i += 256) a.item_unit[(size_t)(c_off + i) * 8 + 3] = v;
   };
   const float* part = a.part + (size_t)c_off * G * (D + 2);
 
