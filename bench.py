@@ -37,6 +37,10 @@ MEASURED_TRAFFIC = {
                     "decode_attn": (9837948 * 2 + 274801) * 1024.0},
     "llama7b_b1": {"sweeps": (717242 * 2 + 16384 + 736650 * 2 + 53248) * 1024.0,
                    "decode_attn": (263969 * 2 + 10228) * 1024.0},
+    "llama7b_b16": {"sweeps": (6642435 * 2 + 131072 + 5898438 * 2 + 425984) * 1024.0,
+                    "decode_attn": (2102048 * 2 + 87862) * 1024.0},
+    "llama13b_b4": {"sweeps": (8408802 * 2 + 204800 + 9147482 * 2 + 665600) * 1024.0,
+                    "decode_attn": (4289956 * 2 + 96794) * 1024.0},
 }
 
 BASELINE_INDEX = {"tiny": 0, "llama7b_b1": 1, "llama7b_b16": 2, "llama13b_b4": 3, "llama65b_b2": 4}
