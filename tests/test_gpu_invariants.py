@@ -22,7 +22,20 @@ def _first_hit(rec, T):
 
 @pytest.mark.parametrize("name,steps", [("llama7b_b1", 6), ("llama7b_b16", 3), ("llama13b_b4", 3), ("llama65b_b2", 2)])
 def test_every_unit_at_full_size(name, steps):
-    w = W[name].scaled(steps=steps)
+    _check_every_unit(W[name].scaled(steps=steps), steps, name)
+
+
+def test_longest_sequence_the_library_accepts():
+    """prompt + generated tokens = 131072 per unit, the limit `fastgen_create` states: five heads
+    with the five planted patterns (so that the adaptive choice spreads over the policies), all
+    properties below and full-cache heads against PyTorch attention over 131072 tokens."""
+    steps = 4
+    w = W["llama7b_b1"].scaled(name="max_len", layers=1, heads=5, batch=1, prompt_len=131072 - steps, steps=steps,
+                               seed=131072)
+    _check_every_unit(w, steps, "longest sequence (n + S = 131072)")
+
+
+def _check_every_unit(w, steps, name):
     n, U, T = w.prompt_len, w.num_units, w.T
     run = H.GpuRun(w, range(U))
     pol, rec, cnt = run.profile_and_compact()
