@@ -299,6 +299,8 @@ def test_decode_step_probe_needs_output_buffer():
     (4, 64, "f32", 97, 10),
     (8, 128, "bf16", 520, 16),
     (3, 64, "bf16", 200, 12),
+    (16, 128, "bf16", 260, 8),     # the largest group the library accepts
+    (16, 128, "f32", 130, 6),
 ])
 def test_grouped_query_heads(G, d, dtype, n, S):
     w = W["llama7b_b1"].scaled(name=f"gqa{G}", layers=1, heads=10, batch=2, prompt_len=n, steps=S, head_dim=d,
